@@ -1,0 +1,220 @@
+"""Seeded synthetic inputs for the MoE-layer workloads.
+
+This module only draws numbers and rounds them to the storage type.  It holds
+none of the layer's arithmetic (no logits, no top-k, no FFN): both the HIP
+path's callers and the CPU oracle's tests take their inputs from here and
+nothing else is shared between the two.
+
+Recipe (per workload, see ``WORKLOADS``):
+  * tokens ``X ~ N(0,1)``, upstream gradient ``dY ~ N(0,1)``;
+  * every weight matrix (gate ``W_g [d,E]``, experts ``W1,W3 [E,d,f]``,
+    ``W2 [E,f,d]``) ``~ N(0, 0.02)`` (0.02 is the standard deviation);
+  * a per-expert additive logit bias ``b_e = -alpha * s * ln(rank_e)`` where
+    ``rank_e`` in 1..E is a seeded permutation of the experts (a Zipf law with
+    exponent ``s`` on the pre-softmax scale); ``alpha`` is a stored constant
+    per workload (calibrated once so that the busiest expert receives the
+    stated multiple of the mean load) and ``dead`` experts get ``-1e4`` so
+    they receive no token at all;
+  * values are drawn in fp32 from numpy's counter-based Philox generator keyed
+    by ``(seed, stream)`` and, for bf16 workloads, rounded to nearest-even
+    bf16.  A bf16 tensor is returned as its uint16 bit pattern.
+
+The MoE layer these inputs feed is the one of the paper's Preliminary section
+(mixture of experts with a top-k softmax gate) with SwiGLU experts as in its
+overlap analysis (section 3.1); the skewed routing stands in for the imbalanced
+token distributions the paper measures on real corpora (Fig. 1).
+"""
+from __future__ import annotations
+
+import json
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, replace
+from typing import Dict, Optional
+
+import numpy as np
+
+# stream ids of the Philox key (seed, stream)
+_S_X, _S_WG, _S_DY, _S_RANK = 1, 2, 3, 4
+_S_W1, _S_W3, _S_W2 = 1000, 2000, 3000  # + expert index
+
+WEIGHT_STD = 0.02
+DEAD_BIAS = -1.0e4
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    T: int          # tokens on this device
+    d: int          # hidden size (H in the paper)
+    f: int          # SwiGLU intermediate size (H' in the paper)
+    E: int          # experts
+    k: int          # top-k
+    dtype: str      # "bf16" or "f32": storage type of X and all weights
+    seed: int
+    zipf_s: float   # exponent of the rank law of the bias
+    alpha: float    # bias scale (calibrated, stored)
+    dead: int = 0   # experts of highest rank forced to receive nothing
+    backward: bool = False
+    target_ratio: Optional[float] = None  # max/mean expert load aimed at
+
+    @property
+    def R(self) -> int:
+        return self.T * self.k
+
+
+def _load_alpha() -> Dict[str, float]:
+    path = os.path.join(os.path.dirname(__file__), "bias_alpha.json")
+    if os.path.exists(path):
+        with open(path) as fh:
+            return {k: float(v["alpha"]) for k, v in json.load(fh).items()}
+    return {}
+
+
+_ALPHA = _load_alpha()
+
+
+def _wl(name, T, d, f, E, k, dtype, seed, zipf_s, alpha=None, **kw) -> Workload:
+    a = _ALPHA.get(name, 1.0) if alpha is None else alpha
+    return Workload(name, T, d, f, E, k, dtype, seed, zipf_s, a, **kw)
+
+
+# The five workloads; alpha of the calibrated ones comes from bias_alpha.json
+# (written by oracle/calibrate_bias.py).  cfg1's bias is fixed by its recipe:
+# 0.5*ln(rank^-1.2) = -0.6*ln(rank)  ->  s = 1.2, alpha = 0.5.
+WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
+    _wl("cfg1_tiny_f32", 256, 128, 256, 8, 2, "f32", 0, 1.2, alpha=0.5),
+    _wl("cfg2_e64k4", 8192, 2048, 1408, 64, 4, "bf16", 1, 1.0, target_ratio=3.0),
+    _wl("cfg3_mixtral", 16384, 4096, 14336, 8, 2, "bf16", 2, 1.0, target_ratio=2.5,
+        backward=True),
+    _wl("cfg4_finegrained", 16384, 2048, 768, 128, 8, "bf16", 3, 1.5, target_ratio=4.0,
+        dead=5, backward=True),
+    _wl("cfg5_skewed", 16384, 4096, 14336, 8, 2, "bf16", 4, 1.0, target_ratio=3.0,
+        backward=True),
+    _wl("cfg5_balanced", 16384, 4096, 14336, 8, 2, "bf16", 4, 1.0, alpha=0.0,
+        backward=True),
+]}
+
+
+def scaled(w: Workload, **changes) -> Workload:
+    """A copy of a workload with some sizes changed (reduced twins for tests)."""
+    return replace(w, **changes)
+
+
+# --------------------------------------------------------------------------
+# storage-type helpers (no arithmetic of the method)
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (nearest, ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns to the fp32 values they denote (exact)."""
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def widen(a: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """The real values a stored tensor denotes, as fp32 or fp64."""
+    v = bf16_bits_to_f32(a) if a.dtype == np.uint16 else a
+    return np.ascontiguousarray(v, dtype=dtype)
+
+
+def _normal(seed: int, stream: int, shape, std: float, dtype: str) -> np.ndarray:
+    g = np.random.Generator(np.random.Philox(key=[seed, stream]))
+    x = g.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        x *= np.float32(std)
+    return f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
+# --------------------------------------------------------------------------
+# tensors
+
+def expert_rank(w: Workload) -> np.ndarray:
+    """rank_e in 1..E: a seeded permutation of the experts."""
+    g = np.random.Generator(np.random.Philox(key=[w.seed, _S_RANK]))
+    return (g.permutation(w.E) + 1).astype(np.int64)
+
+
+def gate_bias(w: Workload, alpha: Optional[float] = None) -> np.ndarray:
+    a = w.alpha if alpha is None else alpha
+    rank = expert_rank(w)
+    b = (-a * w.zipf_s * np.log(rank.astype(np.float64))).astype(np.float32)
+    if w.dead:
+        b[rank > w.E - w.dead] = np.float32(DEAD_BIAS)
+    return b
+
+
+def tokens(w: Workload) -> np.ndarray:
+    return _normal(w.seed, _S_X, (w.T, w.d), 1.0, w.dtype)
+
+
+def upstream_grad(w: Workload) -> np.ndarray:
+    return _normal(w.seed, _S_DY, (w.T, w.d), 1.0, w.dtype)
+
+
+def gate_weight(w: Workload) -> np.ndarray:
+    return _normal(w.seed, _S_WG, (w.d, w.E), WEIGHT_STD, w.dtype)
+
+
+def expert_weights(w: Workload, threads: int = 8):
+    """W1 [E,d,f], W3 [E,d,f], W2 [E,f,d]; one Philox stream per expert matrix."""
+    st = np.uint16 if w.dtype == "bf16" else np.float32
+    W1 = np.empty((w.E, w.d, w.f), st)
+    W3 = np.empty((w.E, w.d, w.f), st)
+    W2 = np.empty((w.E, w.f, w.d), st)
+
+    def fill(job):
+        dst, base, e = job
+        dst[e] = _normal(w.seed, base + e, dst.shape[1:], WEIGHT_STD, w.dtype)
+
+    jobs = [(m, b, e) for e in range(w.E) for m, b in ((W1, _S_W1), (W3, _S_W3), (W2, _S_W2))]
+    if threads > 1 and W1[0].size >= (1 << 20):
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(fill, jobs))
+    else:
+        for j in jobs:
+            fill(j)
+    return W1, W3, W2
+
+
+def layer_inputs(w: Workload, with_experts: bool = True, threads: int = 8) -> Dict[str, np.ndarray]:
+    out = {"x": tokens(w), "w_gate": gate_weight(w), "bias": gate_bias(w)}
+    if w.backward:
+        out["dy"] = upstream_grad(w)
+    if with_experts:
+        out["w1"], out["w3"], out["w2"] = expert_weights(w, threads)
+    return out
+
+
+def skewed_counts(R: int, E: int, ratio: float, T: Optional[int] = None) -> np.ndarray:
+    """Per-expert row counts summing to R with max/mean = ratio (geometric decay).
+
+    Used to drive the grouped FFN directly with a chosen load vector.  No count
+    exceeds T (a token picks an expert at most once)."""
+    if ratio <= 1.0 or E == 1:
+        c = np.full(E, R // E, np.int64)
+        c[: R - c.sum()] += 1
+        return c.astype(np.int32)
+    lo, hi = 0.0, 50.0
+    for _ in range(80):  # find decay g with max/mean = ratio
+        g = 0.5 * (lo + hi)
+        p = np.exp(-g * np.arange(E) / E)
+        if p[0] / p.mean() < ratio:
+            lo = g
+        else:
+            hi = g
+    p = np.exp(-g * np.arange(E) / E)
+    c = np.floor(p / p.sum() * R).astype(np.int64)
+    if T is not None:
+        c = np.minimum(c, T)
+    i = 0
+    while c.sum() < R:  # hand the remainder out round-robin, lightest first
+        j = E - 1 - (i % E)
+        if T is None or c[j] < T:
+            c[j] += 1
+        i += 1
+    return c.astype(np.int32)

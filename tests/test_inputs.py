@@ -1,0 +1,64 @@
+"""The seeded input generators: determinism, storage rounding, and the stated skew."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2602_11686_amd import inputs as I
+
+
+def test_bf16_rounding_matches_library_and_is_idempotent():
+    g = np.random.default_rng(0)
+    x = np.concatenate([g.standard_normal(100000).astype(np.float32) * 3,
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38], np.float32)])
+    bits = I.f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(bits, ref)
+    back = I.bf16_bits_to_f32(bits)
+    np.testing.assert_array_equal(I.f32_to_bf16_bits(back), bits)
+    assert np.abs(back[:100000] - x[:100000]).max() <= np.abs(x[:100000]).max() * 2.0 ** -8
+
+
+def test_generators_are_deterministic_and_streams_differ():
+    w = I.scaled(I.WORKLOADS["cfg2_e64k4"], T=64, d=128, f=64, E=4)
+    a, b = I.layer_inputs(w), I.layer_inputs(w)
+    for n in a:
+        np.testing.assert_array_equal(a[n], b[n])
+    assert not np.array_equal(a["w1"][0], a["w1"][1])
+    assert not np.array_equal(a["w1"][0], a["w3"][0])
+    x = I.widen(a["x"])
+    assert abs(x.std() - 1) < 0.05
+    assert abs(I.widen(a["w1"]).std() - 0.02) < 0.002
+    assert a["x"].dtype == np.uint16
+
+
+def test_cfg1_bias_is_the_fixed_zipf_recipe():
+    w = I.WORKLOADS["cfg1_tiny_f32"]
+    b = I.gate_bias(w)
+    rank = I.expert_rank(w)
+    assert sorted(rank.tolist()) == list(range(1, 9))
+    np.testing.assert_allclose(b, 0.5 * np.log(rank.astype(np.float64) ** -1.2), rtol=1e-6)
+
+
+@pytest.mark.parametrize("name", ["cfg2_e64k4", "cfg3_mixtral", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced"])
+def test_stored_alpha_gives_the_stated_skew(name):
+    w = I.WORKLOADS[name]
+    ids, _, _ = O.gate_topk(I.widen(I.tokens(w)), I.widen(I.gate_weight(w)), I.gate_bias(w), w.k)
+    counts = np.bincount(ids.ravel(), minlength=w.E)
+    mean = w.T * w.k / w.E
+    assert counts.sum() == w.T * w.k
+    if w.target_ratio is not None:
+        assert abs(counts.max() / mean / w.target_ratio - 1) < 0.02
+    else:  # the balanced case of the re-layout comparison: all loads within 5 % of the mean
+        assert np.abs(counts / mean - 1).max() < 0.05
+    assert (counts == 0).sum() == w.dead
+
+
+def test_skewed_counts_helper():
+    for R, E, ratio, T in [(32768, 8, 3.0, 16384), (131072, 128, 4.0, 16384), (1000, 7, 1.0, None)]:
+        c = I.skewed_counts(R, E, ratio, T)
+        assert c.sum() == R and (c >= 0).all()
+        if T:
+            assert c.max() <= T
+        if ratio > 1:
+            assert abs(c.max() / c.mean() / ratio - 1) < 0.03
