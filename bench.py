@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One step = one pass of the hot path over one batch of the named synthetic
+workload: gate -> permute -> grouped FFN forward -> combine, plus (for the
+workloads that train) combine backward -> grouped FFN backward -> permute
+backward -> gate backward.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line.  `value` is tokens/s of the whole step; `roofline` prices
+the grouped-FFN kernels (the dominant ones) against the dense bf16 MFMA peak
+with HIP events recorded around them inside the timed steps; `cpu_baseline` is
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def cpu_baseline(w, inp, target_seconds=15.0):
+    """The oracle (fp32 instantiation, as it stands) on the first Ts tokens of the same workload."""
+    import numpy as np
+    from oracle import oracle as O
+    from paper_2602_11686_amd import inputs as I
+    cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "1000000")))
+    f = {n: I.widen(v, np.float32) for n, v in inp.items()}
+
+    def run(ts):
+        t0 = time.perf_counter()
+        fw = O.layer_fwd(f["x"][:ts], f["w_gate"], f["bias"], f["w1"], f["w3"], f["w2"], w.k)
+        if w.backward:
+            O.layer_bwd(f["x"][:ts], f["w_gate"], f["w1"], f["w3"], f["w2"], fw, f["dy"][:ts])
+        return time.perf_counter() - t0
+
+    ts = min(w.T, 64)
+    dt = run(ts)                                   # probe (also warms the library)
+    ts2 = int(min(w.T, max(ts, ts * target_seconds / max(dt, 1e-3))))
+    ts2 = max(64, ts2 // 64 * 64) if w.T >= 64 else w.T
+    dt2 = run(ts2)
+    return {"value": ts2 / dt2, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {ts2} of {w.T} tokens of {w.name} (all {w.E} experts' weights), "
+                      f"{'fwd+bwd' if w.backward else 'fwd'}, fp32 oracle, {dt2:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2_e64k4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the hot path of one device's token share); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_11686_amd import binding as B
+    from paper_2602_11686_amd import inputs as I
+    from paper_2602_11686_amd.layer import MoeLayerBuffers, to_device
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    B.lib()  # fail loudly if the HIP library is not built
+
+    w = I.WORKLOADS[args.workload]
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    s = B.Shape(w.T, w.d, w.f, w.E, w.k, dt)
+    inp = I.layer_inputs(w)
+    g = {n: (to_device(v, dt) if n != "bias" else torch.from_numpy(v).cuda()) for n, v in inp.items()}
+    buf = MoeLayerBuffers(s, backward=w.backward)
+    torch.cuda.synchronize()
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    stage_names = ["gate", "permute", "ffn_fwd", "combine"] + (
+        ["combine_bwd", "ffn_bwd", "permute_bwd", "gate_bwd"] if w.backward else [])
+    marks = [[ev() for _ in range(len(stage_names) + 1)] for _ in range(args.steps)]
+
+    def step(m=None):
+        def mark(i):
+            if m is not None:
+                m[i].record()
+        mark(0)
+        B.moe_gate_topk(s, g["x"], g["w_gate"], g["bias"], buf.topk_ids, buf.topk_w, None, buf.ws); mark(1)
+        B.moe_permute(s, g["x"], buf.topk_ids, buf.counts, buf.offsets, buf.row_of_pair, buf.pair_of_row,
+                      buf.x_perm, buf.ws); mark(2)
+        B.moe_grouped_ffn_fwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.y_perm, buf.a_save,
+                              buf.b_save, buf.ws); mark(3)
+        B.moe_unpermute_combine(s, buf.y_perm, buf.row_of_pair, buf.topk_w, buf.y); mark(4)
+        if w.backward:
+            B.moe_combine_bwd(s, g["dy"], buf.y_perm, buf.row_of_pair, buf.topk_w, buf.dy_perm, buf.dtopk_w); mark(5)
+            B.moe_grouped_ffn_bwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.a_save, buf.b_save,
+                                  buf.dy_perm, buf.dx_perm, buf.dw1, buf.dw3, buf.dw2, buf.ws); mark(6)
+            B.moe_unpermute_combine(s, buf.dx_perm, buf.row_of_pair, None, buf.dx); mark(7)
+            B.moe_gate_topk_bwd(s, g["x"], g["w_gate"], buf.topk_ids, buf.topk_w, buf.dtopk_w, buf.dx,
+                                buf.dw_gate, buf.ws); mark(8)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(marks[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    stage_ms = {n: float(np.mean([marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(args.steps)]))
+                for j, n in enumerate(stage_names)}
+    counts = buf.counts.cpu().numpy()
+    R, el = w.T * w.k, (2 if w.dtype == "bf16" else 4)
+
+    # algorithmic work (not padded tiles, not recomputation)
+    ffn_fwd_flops = 6.0 * w.d * w.f * R
+    ffn_bwd_flops = 12.0 * w.d * w.f * R
+    flops = ffn_fwd_flops + (ffn_bwd_flops if w.backward else 0.0)
+    ffn_ms = stage_ms["ffn_fwd"] + (stage_ms["ffn_bwd"] if w.backward else 0.0)
+    achieved = flops / (ffn_ms * 1e-3) / 1e12
+    perm_bytes = (1 + w.k) * w.T * w.d * el + R * 12
+    comb_bytes = (1 + w.k) * w.T * w.d * el + R * 8
+    stages = {n: {"ms": round(v, 4)} for n, v in stage_ms.items()}
+    stages["ffn_fwd"]["tflops"] = round(ffn_fwd_flops / (stage_ms["ffn_fwd"] * 1e-3) / 1e12, 2)
+    stages["permute"]["gbs"] = round(perm_bytes / (stage_ms["permute"] * 1e-3) / 1e9, 1)
+    stages["combine"]["gbs"] = round(comb_bytes / (stage_ms["combine"] * 1e-3) / 1e9, 1)
+    if w.backward:
+        stages["ffn_bwd"]["tflops"] = round(ffn_bwd_flops / (stage_ms["ffn_bwd"] * 1e-3) / 1e12, 2)
+        stages["permute_bwd"]["gbs"] = round(comb_bytes / (stage_ms["permute_bwd"] * 1e-3) / 1e9, 1)
+        stages["combine_bwd"]["gbs"] = round(((1 + 2 * w.k) * w.T * w.d * el) / (stage_ms["combine_bwd"] * 1e-3) / 1e9, 1)
+
+    out = {
+        "metric": "MoE-layer tokens/s; grouped-GEMM bf16 TFLOP/s and % MFMA peak, 1 GPU",
+        "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "T": w.T, "d": w.d, "f": w.f, "E": w.E, "k": w.k,
+                   "pass": "fwd+bwd" if w.backward else "fwd", "seed": w.seed,
+                   "max_over_mean_load": float(counts.max() / counts.mean()),
+                   "empty_experts": int((counts == 0).sum())},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "grouped FFN (moe_grouped_ffn_fwd" + ("+bwd" if w.backward else "") + ")",
+                     "flops_per_launch": flops, "ms_per_launch": ffn_ms},
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,287 @@
+// Gate of the MoE layer: moe_gate_topk and moe_gate_topk_bwd.
+//
+// g(x) = Softmax(TopK(x * W_g)) (paper, Preliminary section).  Logits are
+// accumulated in fp32 from exact products of the stored values, a per-expert
+// bias is added, and the k largest are picked by a wavefront: every lane holds
+// the logits of the experts (lane, lane+64, ...), k rounds of a 64-lane
+// arg-max (value descending, expert index ascending on ties) pick the slots in
+// order, and the softmax runs over the k picked values only.
+#include "moe_internal.h"
+
+namespace moe {
+
+constexpr int kGateTokens = 16;   // tokens per workgroup
+constexpr int kGateKC = 256;      // hidden-dimension chunk staged in LDS
+constexpr int kGateMaxNE = MOE_MAX_EXPERTS / 64;
+
+size_t gate_workspace_bytes(const moe_shape*) { return 256; }
+
+// One workgroup = 4 wavefronts = 16 tokens; wave w owns tokens w, w+4, w+8, w+12
+// of the block, lane l owns experts l, l+64, ...
+template <class T>
+__global__ __launch_bounds__(256) void gate_topk_kernel(const T* __restrict__ x, const T* __restrict__ wg,
+                                                        const float* __restrict__ bias, int32_t* __restrict__ ids,
+                                                        float* __restrict__ wout, float* __restrict__ logits_out,
+                                                        int Tn, int d, int E, int k) {
+    __shared__ float xs[kGateTokens][kGateKC];
+    __shared__ float sel[4][MOE_MAX_EXPERTS];  // per wave: the picked logits of the token in flight
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t0 = blockIdx.x * kGateTokens;
+    const int ne = (E + 63) >> 6;
+
+    float acc[4][kGateMaxNE];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < kGateMaxNE; ++j) acc[i][j] = 0.f;
+
+    for (int c0 = 0; c0 < d; c0 += kGateKC) {
+        const int kc = min(kGateKC, d - c0);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < kGateTokens * kGateKC; idx += 256) {
+            const int tt = idx / kGateKC, c = idx - tt * kGateKC;
+            const int t = t0 + tt;
+            xs[tt][c] = (t < Tn && c < kc) ? Elem<T>::load(x + (size_t)t * d + c0 + c) : 0.f;
+        }
+        __syncthreads();
+        for (int c = 0; c < kc; ++c) {
+            float wv[kGateMaxNE];
+#pragma unroll
+            for (int j = 0; j < kGateMaxNE; ++j) {
+                const int e = lane + 64 * j;
+                wv[j] = (j < ne && e < E) ? Elem<T>::load(wg + (size_t)(c0 + c) * E + e) : 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float xv = xs[wave + 4 * i][c];
+#pragma unroll
+                for (int j = 0; j < kGateMaxNE; ++j) acc[i][j] = fmaf(xv, wv[j], acc[i][j]);
+            }
+        }
+    }
+
+    // top-k and softmax, one token at a time per wave
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = t0 + wave + 4 * i;
+        if (t >= Tn) continue;  // uniform per wave
+        float v[kGateMaxNE];
+#pragma unroll
+        for (int j = 0; j < kGateMaxNE; ++j) {
+            const int e = lane + 64 * j;
+            if (e < E) {
+                v[j] = acc[i][j] + (bias ? bias[e] : 0.f);
+                if (logits_out) logits_out[(size_t)t * E + e] = v[j];
+            } else {
+                v[j] = -INFINITY;
+            }
+        }
+        for (int s = 0; s < k; ++s) {
+            // lane-local best (lowest index first on ties: j ascending, strict >)
+            float bv = v[0];
+            int be = lane;
+#pragma unroll
+            for (int j = 1; j < kGateMaxNE; ++j)
+                if (v[j] > bv) { bv = v[j]; be = lane + 64 * j; }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                const float ov = __shfl_xor(bv, m, 64);
+                const int oe = __shfl_xor(be, m, 64);
+                if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+            }
+            // every lane now holds the same winner
+            if ((be & 63) == lane) {
+#pragma unroll
+                for (int j = 0; j < kGateMaxNE; ++j)
+                    if (be == lane + 64 * j) v[j] = -INFINITY;
+            }
+            if (lane == 0) {
+                ids[(size_t)t * k + s] = be;
+                sel[wave][s] = bv;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        const float m0 = sel[wave][0];
+        float z = 0.f;
+        for (int s = 0; s < k; ++s) z += __expf(sel[wave][s] - m0);
+        for (int s = lane; s < k; s += 64) wout[(size_t)t * k + s] = __expf(sel[wave][s] - m0) / z;
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---- backward -----------------------------------------------------------------------
+
+// wgT[e][c] = w_gate[c][e] as fp32 (makes the dx update a contiguous read)
+template <class T>
+__global__ void gate_transpose_kernel(const T* __restrict__ wg, float* __restrict__ wgT, int d, int E) {
+    const int64_t n = (int64_t)d * E;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int e = (int)(i / d), c = (int)(i - (int64_t)e * d);
+        wgT[i] = Elem<T>::load(wg + (size_t)c * E + e);
+    }
+}
+
+// dl[t,s] = w_s (dw_s - sum_j w_j dw_j)
+__global__ void gate_dl_kernel(const float* __restrict__ w, const float* __restrict__ dw, float* __restrict__ dl,
+                               int Tn, int k) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= Tn) return;
+    float dot = 0.f;
+    for (int s = 0; s < k; ++s) dot += w[(size_t)t * k + s] * dw[(size_t)t * k + s];
+    for (int s = 0; s < k; ++s) dl[(size_t)t * k + s] = w[(size_t)t * k + s] * (dw[(size_t)t * k + s] - dot);
+}
+
+// dx[t,c] += sum_s dl[t,s] * wgT[ids[t,s]][c]      (4 columns per thread)
+template <class T>
+__global__ __launch_bounds__(256) void gate_bwd_dx_kernel(T* __restrict__ dx, const float* __restrict__ wgT,
+                                                          const int32_t* __restrict__ ids,
+                                                          const float* __restrict__ dl, int Tn, int d, int k) {
+    const int q = d / 4;
+    const int64_t total = (int64_t)Tn * q;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int t = (int)(i / q), c = (int)(i - (int64_t)t * q) * 4;
+        float a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = Elem<T>::load(dx + (size_t)t * d + c + j);
+        for (int s = 0; s < k; ++s) {
+            const float g = dl[(size_t)t * k + s];
+            const float4 wv = *reinterpret_cast<const float4*>(wgT + (size_t)ids[(size_t)t * k + s] * d + c);
+            a[0] = fmaf(g, wv.x, a[0]); a[1] = fmaf(g, wv.y, a[1]);
+            a[2] = fmaf(g, wv.z, a[2]); a[3] = fmaf(g, wv.w, a[3]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) Elem<T>::store(dx + (size_t)t * d + c + j, a[j]);
+    }
+}
+
+// partial[chunk][e][c] = sum over the chunk's tokens of x[t,c] * dL[t,e]; a thread
+// owns one column c of a slab, the accumulators of all experts live in LDS.
+constexpr int kDwgSlab = 128;    // columns per workgroup (= threads)
+constexpr int kDwgTokens = 256;  // tokens per chunk
+
+template <class T>
+__global__ __launch_bounds__(kDwgSlab) void gate_bwd_dwg_partial_kernel(
+    const T* __restrict__ x, const int32_t* __restrict__ ids, const float* __restrict__ dl,
+    float* __restrict__ partial, int Tn, int d, int E, int k) {
+    extern __shared__ float accs[];  // [E][kDwgSlab]
+    const int c = blockIdx.x * kDwgSlab + threadIdx.x;
+    const int chunk = blockIdx.y;
+    for (int e = 0; e < E; ++e) accs[e * kDwgSlab + threadIdx.x] = 0.f;
+    const int t1 = min(Tn, (chunk + 1) * kDwgTokens);
+    if (c < d) {
+        for (int t = chunk * kDwgTokens; t < t1; ++t) {
+            const float xv = Elem<T>::load(x + (size_t)t * d + c);
+            for (int s = 0; s < k; ++s) {
+                const int e = ids[(size_t)t * k + s];
+                accs[e * kDwgSlab + threadIdx.x] += xv * dl[(size_t)t * k + s];
+            }
+        }
+        for (int e = 0; e < E; ++e)
+            partial[((size_t)chunk * E + e) * d + c] = accs[e * kDwgSlab + threadIdx.x];
+    }
+}
+
+// dw_gate[c][e] = sum over chunks, in chunk order
+__global__ void gate_bwd_dwg_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwg, int nchunks,
+                                           int d, int E) {
+    const int64_t n = (int64_t)d * E;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int e = (int)(i / d), c = (int)(i - (int64_t)e * d);
+        float a = 0.f;
+        for (int ch = 0; ch < nchunks; ++ch) a += partial[((size_t)ch * E + e) * d + c];
+        dwg[(size_t)c * E + e] = a;
+    }
+}
+
+static inline int dwg_chunks(int Tn) { return (Tn + kDwgTokens - 1) / kDwgTokens; }
+
+size_t gate_bwd_workspace_bytes(const moe_shape* s) {
+    size_t b = align_up((size_t)s->E * s->d * 4, 256);                 // wgT
+    b += align_up((size_t)s->T * s->k * 4, 256);                       // dl
+    b += align_up((size_t)dwg_chunks(s->T) * s->E * s->d * 4, 256);    // partial sums
+    return b;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" moe_status moe_gate_topk(const moe_shape* s, const void* x, const void* w_gate, const float* bias,
+                                    int32_t* topk_ids, float* topk_w, float* logits_out, void* ws, size_t ws_bytes,
+                                    void* stream) {
+    const char* who = "moe_gate_topk";
+    MOE_RETURN_IF(check_shape(s, who));
+    MOE_RETURN_IF(check_ptr(x, "x", who));
+    MOE_RETURN_IF(check_ptr(w_gate, "w_gate", who));
+    MOE_RETURN_IF(check_ptr(bias, "bias", who, true));
+    MOE_RETURN_IF(check_ptr(topk_ids, "topk_ids", who));
+    MOE_RETURN_IF(check_ptr(topk_w, "topk_w", who));
+    MOE_RETURN_IF(check_ptr(logits_out, "logits_out", who, true));
+    (void)ws;
+    (void)ws_bytes;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int grid = (s->T + kGateTokens - 1) / kGateTokens;
+    if (s->dtype == MOE_BF16)
+        gate_topk_kernel<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(x),
+                                                       static_cast<const bf16_t*>(w_gate), bias, topk_ids, topk_w,
+                                                       logits_out, s->T, s->d, s->E, s->k);
+    else
+        gate_topk_kernel<float><<<grid, 256, 0, st>>>(static_cast<const float*>(x),
+                                                      static_cast<const float*>(w_gate), bias, topk_ids, topk_w,
+                                                      logits_out, s->T, s->d, s->E, s->k);
+    return launch_status(who);
+}
+
+template <class T>
+static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gate, const int32_t* ids,
+                                  const float* w, const float* dw, T* dx, float* dwg, void* ws, hipStream_t st) {
+    Carver cv(ws);
+    float* wgT = static_cast<float*>(cv.take((size_t)s->E * s->d * 4));
+    float* dl = static_cast<float*>(cv.take((size_t)s->T * s->k * 4));
+    const int nchunks = dwg_chunks(s->T);
+    float* partial = static_cast<float*>(cv.take((size_t)nchunks * s->E * s->d * 4));
+    gate_dl_kernel<<<(s->T + 255) / 256, 256, 0, st>>>(w, dw, dl, s->T, s->k);
+    if (dx) {
+        gate_transpose_kernel<T><<<256, 256, 0, st>>>(w_gate, wgT, s->d, s->E);
+        int64_t items = (int64_t)s->T * (s->d / 4);
+        int grid = (int)((items + 255) / 256 > 4096 ? 4096 : (items + 255) / 256);
+        gate_bwd_dx_kernel<T><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, s->T, s->d, s->k);
+    }
+    const size_t lds = (size_t)s->E * kDwgSlab * sizeof(float);
+    static thread_local bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_bwd_dwg_partial_kernel<T>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, MOE_MAX_EXPERTS * kDwgSlab * 4);
+        attr_set = true;
+    }
+    dim3 grid((s->d + kDwgSlab - 1) / kDwgSlab, nchunks);
+    gate_bwd_dwg_partial_kernel<T><<<grid, kDwgSlab, lds, st>>>(x, ids, dl, partial, s->T, s->d, s->E, s->k);
+    gate_bwd_dwg_reduce_kernel<<<256, 256, 0, st>>>(partial, dwg, nchunks, s->d, s->E);
+    return launch_status("moe_gate_topk_bwd");
+}
+
+extern "C" moe_status moe_gate_topk_bwd(const moe_shape* s, const void* x, const void* w_gate,
+                                        const int32_t* topk_ids, const float* topk_w, const float* dtopk_w,
+                                        void* dx_inout, float* dw_gate, void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "moe_gate_topk_bwd";
+    MOE_RETURN_IF(check_shape(s, who));
+    MOE_RETURN_IF(check_ptr(x, "x", who));
+    MOE_RETURN_IF(check_ptr(w_gate, "w_gate", who));
+    MOE_RETURN_IF(check_ptr(topk_ids, "topk_ids", who));
+    MOE_RETURN_IF(check_ptr(topk_w, "topk_w", who));
+    MOE_RETURN_IF(check_ptr(dtopk_w, "dtopk_w", who));
+    MOE_RETURN_IF(check_ptr(dx_inout, "dx_inout", who, true));
+    MOE_RETURN_IF(check_ptr(dw_gate, "dw_gate", who));
+    MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    if (ws_bytes < gate_bwd_workspace_bytes(s)) {
+        set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, gate_bwd_workspace_bytes(s));
+        return MOE_ERR_WORKSPACE_TOO_SMALL;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (s->dtype == MOE_BF16)
+        return gate_bwd_launch<bf16_t>(s, static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w_gate), topk_ids,
+                                       topk_w, dtopk_w, static_cast<bf16_t*>(dx_inout), dw_gate, ws, st);
+    return gate_bwd_launch<float>(s, static_cast<const float*>(x), static_cast<const float*>(w_gate), topk_ids, topk_w,
+                                  dtopk_w, static_cast<float*>(dx_inout), dw_gate, ws, st);
+}

@@ -1,0 +1,74 @@
+// Internal helpers shared by the HIP translation units of libmoe (host-side
+// validation, error text, launch checks, bf16 conversion).  Not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "moe.h"
+
+namespace moe {
+
+void set_error(const char* fmt, ...);
+moe_status check_shape(const moe_shape* s, const char* who);
+bool aligned16(const void* p);
+moe_status check_ptr(const void* p, const char* name, const char* who, bool nullable = false);
+moe_status launch_status(const char* who);
+
+inline size_t el_size(const moe_shape* s) { return s->dtype == MOE_BF16 ? 2 : 4; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Workspace layout of the grouped FFN calls: carve regions off one buffer.
+struct Carver {
+    char* base;
+    size_t used = 0;
+    explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+    void* take(size_t bytes) {
+        void* r = base ? base + used : nullptr;
+        used += align_up(bytes, 256);
+        return r;
+    }
+};
+
+size_t gate_workspace_bytes(const moe_shape* s);
+size_t permute_workspace_bytes(const moe_shape* s);
+size_t ffn_fwd_workspace_bytes(const moe_shape* s);
+size_t ffn_bwd_workspace_bytes(const moe_shape* s);
+size_t gate_bwd_workspace_bytes(const moe_shape* s);
+
+// ---- device-side element helpers -------------------------------------------
+typedef uint16_t bf16_t;  // raw bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round to nearest, ties to even (inputs are finite by contract)
+__device__ __forceinline__ bf16_t f32_to_bf16(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <class T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+__device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)); }
+__device__ __forceinline__ float silu_grad_f(float a) {
+    float s = 1.0f / (1.0f + __expf(-a));
+    return s * (1.0f + a * (1.0f - s));
+}
+
+}  // namespace moe
+
+#define MOE_RETURN_IF(expr)                    \
+    do {                                       \
+        moe_status _st = (expr);               \
+        if (_st != MOE_OK) return _st;         \
+    } while (0)

@@ -1,0 +1,324 @@
+// Token rearrangement by expert and its inverse: moe_permute,
+// moe_unpermute_combine, moe_combine_bwd.
+//
+// The paper's implementation section replaces a host-blocking masked select by
+// a device kernel for "token rearrangement"; the combine is the weighted sum of
+// the mixture formula (Preliminary section).  Everything here is HBM-bound
+// copy work plus a small integer sort, so the kernels move rows as 16-byte
+// vectors, read each token row once, and keep all counts on the device.
+//
+// Stable counting sort of the R = T*k pairs, in three small kernels:
+//   1. per-chunk histograms (one wavefront owns CHUNK consecutive pairs),
+//   2. one workgroup turns them into per-chunk starting rows (exclusive scan
+//      down the chunks for every expert, then across experts),
+//   3. each wavefront walks its chunk in order, 64 pairs at a time: lanes with
+//      the same expert are found with 8 ballots over the bits of the expert id,
+//      the lane's rank is the running count of its expert plus the number of
+//      lower lanes in its group.
+// A fourth kernel copies the rows: one pass over x, k row writes per token.
+#include "moe_internal.h"
+
+namespace moe {
+
+constexpr int kChunk = 512;        // pairs per wavefront in the sort
+constexpr int kWavesPerBlock = 4;  // 256 threads
+
+static inline int num_chunks(int64_t R) { return (int)((R + kChunk - 1) / kChunk); }
+
+size_t permute_workspace_bytes(const moe_shape* s) {
+    const int64_t R = (int64_t)s->T * s->k;
+    return align_up((size_t)num_chunks(R) * s->E * sizeof(int32_t), 256);
+}
+
+// ---- 1. per-chunk histogram ---------------------------------------------------
+__global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __restrict__ ids, int R, int E,
+                                                           int32_t* __restrict__ chunk_hist) {
+    extern __shared__ int32_t lds_hist[];  // [kWavesPerBlock][E]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int32_t* h = lds_hist + wave * E;
+    for (int e = lane; e < E; e += 64) h[e] = 0;
+    __syncthreads();
+    const int chunk = blockIdx.x * kWavesPerBlock + wave;
+    const int p0 = chunk * kChunk;
+    for (int i = lane; i < kChunk; i += 64) {
+        const int p = p0 + i;
+        if (p < R) atomicAdd(&h[ids[p]], 1);
+    }
+    __syncthreads();
+    if (p0 < R)
+        for (int e = lane; e < E; e += 64) chunk_hist[(size_t)chunk * E + e] = h[e];
+}
+
+// ---- 2. scan: chunk_hist[c][e] becomes the first row of chunk c for expert e -----
+__global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__ chunk_hist, int nchunks, int E,
+                                                           int32_t* __restrict__ counts,
+                                                           int32_t* __restrict__ offsets) {
+    __shared__ int32_t cnt[MOE_MAX_EXPERTS];
+    __shared__ int32_t off[MOE_MAX_EXPERTS + 1];
+    const int e = threadIdx.x;
+    if (e < E) {
+        int32_t run = 0;
+        for (int c = 0; c < nchunks; ++c) {
+            const int32_t v = chunk_hist[(size_t)c * E + e];
+            chunk_hist[(size_t)c * E + e] = run;
+            run += v;
+        }
+        cnt[e] = run;
+        counts[e] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int32_t run = 0;
+        for (int i = 0; i < E; ++i) {
+            off[i] = run;
+            run += cnt[i];
+        }
+        off[E] = run;
+    }
+    __syncthreads();
+    if (e < E) offsets[e] = off[e];
+    if (e == 0) offsets[E] = off[E];
+    if (e < E) {
+        const int32_t o = off[e];
+        for (int c = 0; c < nchunks; ++c) chunk_hist[(size_t)c * E + e] += o;
+    }
+}
+
+// ---- 3. stable rank of every pair ---------------------------------------------------
+__global__ __launch_bounds__(256) void permute_rank_kernel(const int32_t* __restrict__ ids, int R, int E,
+                                                           const int32_t* __restrict__ chunk_base,
+                                                           int32_t* __restrict__ row_of_pair,
+                                                           int32_t* __restrict__ pair_of_row) {
+    extern __shared__ int32_t lds_next[];  // [kWavesPerBlock][E] next free row per expert
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * kWavesPerBlock + wave;
+    const int p0 = chunk * kChunk;
+    if (p0 >= R) return;  // whole wavefront leaves together; no barrier below
+    int32_t* next = lds_next + wave * E;
+    for (int e = lane; e < E; e += 64) next[e] = chunk_base[(size_t)chunk * E + e];
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    for (int i = 0; i < kChunk; i += 64) {
+        const int p = p0 + i + lane;
+        const bool live = p < R;
+        const int e = live ? ids[p] : -1;
+        uint64_t same = __ballot(live);
+        if (!live) same = 0;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t bal = __ballot((e >> b) & 1);
+            same &= ((e >> b) & 1) ? bal : ~bal;
+        }
+        if (live) {
+            const int before = __popcll(same & lt_mask);
+            const int row = next[e] + before;
+            row_of_pair[p] = row;
+            pair_of_row[row] = p;
+        }
+        // the highest lane of each group advances the expert's counter; the wave
+        // executes in lockstep, so all reads above precede these writes
+        __builtin_amdgcn_wave_barrier();
+        if (live && (same >> lane) == 1ull) next[e] += __popcll(same);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---- 4. row scatter: x[t] -> x_perm[row_of_pair[t*k+s]] for s < k ----------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void permute_scatter_rows_kernel(const u32x4* __restrict__ x,
+                                                                   const int32_t* __restrict__ row_of_pair,
+                                                                   u32x4* __restrict__ x_perm, int T, int k,
+                                                                   int vecs_per_row) {
+    const int64_t total = (int64_t)T * vecs_per_row;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int t = (int)(i / vecs_per_row);
+        const int v = (int)(i - (int64_t)t * vecs_per_row);
+        const u32x4 val = __builtin_nontemporal_load(&x[i]);
+        for (int s = 0; s < k; ++s) {
+            const int row = row_of_pair[(size_t)t * k + s];
+            __builtin_nontemporal_store(val, &x_perm[(size_t)row * vecs_per_row + v]);
+        }
+    }
+}
+
+// ---- combine: y[t] = sum_s w[t,s] * y_perm[row_of_pair[t*k+s]] ------------------------
+template <class T, int VEC>
+struct VecIO;
+template <>
+struct VecIO<bf16_t, 8> {
+    static __device__ __forceinline__ void load(const void* p, float (&v)[8]) {
+        const uint4 u = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(void* p, const float (&v)[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <>
+struct VecIO<float, 4> {
+    static __device__ __forceinline__ void load(const void* p, float (&v)[4]) {
+        const float4 u = *reinterpret_cast<const float4*>(p);
+        v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+    }
+    static __device__ __forceinline__ void store(void* p, const float (&v)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+
+template <class T, int VEC>
+__global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_perm,
+                                                      const int32_t* __restrict__ row_of_pair,
+                                                      const float* __restrict__ w, T* __restrict__ y, int Tn,
+                                                      int d, int k) {
+    const int vecs_per_row = d / VEC;
+    const int64_t total = (int64_t)Tn * vecs_per_row;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int t = (int)(i / vecs_per_row);
+        const int v = (int)(i - (int64_t)t * vecs_per_row);
+        float acc[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+        for (int s = 0; s < k; ++s) {
+            const int row = row_of_pair[(size_t)t * k + s];
+            const float ws = w ? w[(size_t)t * k + s] : 1.0f;
+            float val[VEC];
+            VecIO<T, VEC>::load(y_perm + (size_t)row * d + (size_t)v * VEC, val);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] += ws * val[j];
+        }
+        VecIO<T, VEC>::store(y + (size_t)t * d + (size_t)v * VEC, acc);
+    }
+}
+
+// ---- combine backward: one wavefront per token -----------------------------------
+template <class T, int VEC>
+__global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ y_perm,
+                                                          const int32_t* __restrict__ row_of_pair,
+                                                          const float* __restrict__ w, T* __restrict__ dy_perm,
+                                                          float* __restrict__ dw, int Tn, int d, int k) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    const int vecs_per_row = d / VEC;
+    for (int s = 0; s < k; ++s) {
+        const int row = row_of_pair[(size_t)t * k + s];
+        const float ws = w[(size_t)t * k + s];
+        float dot = 0.f;
+        for (int v = lane; v < vecs_per_row; v += 64) {
+            float g[VEC], yv[VEC], o[VEC];
+            VecIO<T, VEC>::load(dy + (size_t)t * d + (size_t)v * VEC, g);
+            VecIO<T, VEC>::load(y_perm + (size_t)row * d + (size_t)v * VEC, yv);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                dot += g[j] * yv[j];
+                o[j] = ws * g[j];
+            }
+            VecIO<T, VEC>::store(dy_perm + (size_t)row * d + (size_t)v * VEC, o);
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
+        if (lane == 0) dw[(size_t)t * k + s] = dot;
+    }
+}
+
+static inline int grid_for(int64_t work_items, int block, int max_blocks) {
+    int64_t g = (work_items + block - 1) / block;
+    if (g > max_blocks) g = max_blocks;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32_t* topk_ids, int32_t* counts,
+                                  int32_t* offsets, int32_t* row_of_pair, int32_t* pair_of_row, void* x_perm,
+                                  void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "moe_permute";
+    MOE_RETURN_IF(check_shape(s, who));
+    MOE_RETURN_IF(check_ptr(topk_ids, "topk_ids", who));
+    MOE_RETURN_IF(check_ptr(counts, "counts", who));
+    MOE_RETURN_IF(check_ptr(offsets, "offsets", who));
+    MOE_RETURN_IF(check_ptr(row_of_pair, "row_of_pair", who));
+    MOE_RETURN_IF(check_ptr(pair_of_row, "pair_of_row", who));
+    MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who, true));
+    if (x_perm) MOE_RETURN_IF(check_ptr(x, "x", who));
+    MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    if (ws_bytes < permute_workspace_bytes(s)) {
+        set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, permute_workspace_bytes(s));
+        return MOE_ERR_WORKSPACE_TOO_SMALL;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int R = s->T * s->k, E = s->E;
+    const int nchunks = num_chunks(R);
+    const int nblocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
+    int32_t* chunk_hist = static_cast<int32_t*>(ws);
+    const size_t lds = (size_t)kWavesPerBlock * E * sizeof(int32_t);
+    permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_hist);
+    permute_scan_kernel<<<1, 256, 0, st>>>(chunk_hist, nchunks, E, counts, offsets);
+    permute_rank_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_hist, row_of_pair, pair_of_row);
+    if (x_perm) {
+        const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
+        const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);
+        permute_scatter_rows_kernel<<<grid, 256, 0, st>>>(static_cast<const u32x4*>(x), row_of_pair,
+                                                          static_cast<u32x4*>(x_perm), s->T, s->k, vecs_per_row);
+    }
+    return launch_status(who);
+}
+
+extern "C" moe_status moe_unpermute_combine(const moe_shape* s, const void* y_perm, const int32_t* row_of_pair,
+                                            const float* topk_w, void* y, void* stream) {
+    const char* who = "moe_unpermute_combine";
+    MOE_RETURN_IF(check_shape(s, who));
+    MOE_RETURN_IF(check_ptr(y_perm, "y_perm", who));
+    MOE_RETURN_IF(check_ptr(row_of_pair, "row_of_pair", who));
+    MOE_RETURN_IF(check_ptr(topk_w, "topk_w", who, true));
+    MOE_RETURN_IF(check_ptr(y, "y", who));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (s->dtype == MOE_BF16) {
+        const int grid = grid_for((int64_t)s->T * (s->d / 8), 256, 256 * 16);
+        combine_kernel<bf16_t, 8><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(y_perm), row_of_pair, topk_w,
+                                                        static_cast<bf16_t*>(y), s->T, s->d, s->k);
+    } else {
+        const int grid = grid_for((int64_t)s->T * (s->d / 4), 256, 256 * 16);
+        combine_kernel<float, 4><<<grid, 256, 0, st>>>(static_cast<const float*>(y_perm), row_of_pair, topk_w,
+                                                       static_cast<float*>(y), s->T, s->d, s->k);
+    }
+    return launch_status(who);
+}
+
+extern "C" moe_status moe_combine_bwd(const moe_shape* s, const void* dy, const void* y_perm,
+                                      const int32_t* row_of_pair, const float* topk_w, void* dy_perm,
+                                      float* dtopk_w, void* stream) {
+    const char* who = "moe_combine_bwd";
+    MOE_RETURN_IF(check_shape(s, who));
+    MOE_RETURN_IF(check_ptr(dy, "dy", who));
+    MOE_RETURN_IF(check_ptr(y_perm, "y_perm", who));
+    MOE_RETURN_IF(check_ptr(row_of_pair, "row_of_pair", who));
+    MOE_RETURN_IF(check_ptr(topk_w, "topk_w", who));
+    MOE_RETURN_IF(check_ptr(dy_perm, "dy_perm", who));
+    MOE_RETURN_IF(check_ptr(dtopk_w, "dtopk_w", who));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int grid = (s->T + 3) / 4;
+    if (s->dtype == MOE_BF16)
+        combine_bwd_kernel<bf16_t, 8><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(dy),
+                                                            static_cast<const bf16_t*>(y_perm), row_of_pair, topk_w,
+                                                            static_cast<bf16_t*>(dy_perm), dtopk_w, s->T, s->d, s->k);
+    else
+        combine_bwd_kernel<float, 4><<<grid, 256, 0, st>>>(static_cast<const float*>(dy),
+                                                           static_cast<const float*>(y_perm), row_of_pair, topk_w,
+                                                           static_cast<float*>(dy_perm), dtopk_w, s->T, s->d, s->k);
+    return launch_status(who);
+}
