@@ -1,0 +1,299 @@
+// Grouped bf16 GEMM for CDNA4 (gfx950): 256x256x64 workgroup tiles, 8 wavefronts,
+// MFMA 32x32x16 bf16 with fp32 accumulators, operands streamed HBM -> LDS by the
+// DMA path of the global loads (no register staging), double-buffered.
+//
+// The ragged dimension is M (the rows of one expert): forward and dgrad GEMMs of
+// the expert FFN (paper section 3.1; 6*H*H' FLOPs per routed token forward).
+//
+//   A  [rows][K]   K contiguous       (activations: Xp, H, dYp, dA, dB)
+//   B  BT == 0: [K][N]  N contiguous  (forward:  W1, W3 [d][f], W2 [f][d])
+//      BT == 1: [N][K]  K contiguous  (dgrad:    W2 as [f][d], W1/W3 as [d][f])
+//
+// LDS layout (one 64 KB stage = A tile + B tile, two stages):
+//   A tile: 256 rows x 128 B.  The 16-byte piece p of row r sits in slot p ^ ((r >> 1) & 7),
+//           so the 16 rows a quarter of an MFMA operand read touches cover 256 B of banks once.
+//   B tile, BT == 1: same as A (256 columns of N as rows).
+//   B tile, BT == 0: 64 k-rows x 512 B.  Piece p of k-row q sits in slot
+//           p ^ (2*(q&3) + 8*(q&1)); operands are read with the transposing LDS read
+//           (ds_read_b64_tr_b16), which hands lane i of a 16-lane group column i of
+//           a 4(k) x 16(n) block.
+// A DMA load writes 64 lanes x 16 B to consecutive LDS addresses, so the swizzle
+// is applied on the global side: lane l fetches the piece that belongs in slot l.
+//
+// DUAL (forward 1): the B tile holds 128 columns of W1 next to the same 128
+// columns of W3; each wavefront accumulates a = x*W1 and b = x*W3 for the same
+// outputs and the epilogue writes silu(a)*b.
+#pragma once
+
+namespace moe {
+
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int kStageBytes = 65536;  // 32 KB A + 32 KB B
+constexpr int kGemmLds = 2 * kStageBytes;
+
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+#define LDS_AS __attribute__((address_space(3)))
+#define GLB_AS __attribute__((address_space(1)))
+
+// slot = piece ^ swz: chosen so that the rows one LDS read instruction touches fall into different banks
+__device__ __forceinline__ int swz_rows(int row) { return (row >> 1) & 7; }              // 128-byte rows, b128 reads
+__device__ __forceinline__ int swz_krow(int q) { return 2 * (q & 3) + 8 * (q & 1); }      // 512-byte k-rows, tr reads
+
+// 16 bytes per lane, global -> LDS, without passing through registers: lane l lands at
+// lds_addr + 16*l (lds_addr is wave-uniform and travels in M0).  Written as inline assembly so
+// that the compiler does not serialise later LDS reads of the *other* stage behind it; the
+// kernel waits for these loads itself (s_waitcnt vmcnt) before the barrier that publishes a stage.
+__device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc)
+                 : "memory", "m0");
+}
+
+// Logical tile id -> (expert, m-tile, n-tile).  Order: expert-major; inside an expert the
+// n-tiles are walked in super-columns of kSuperN, m-tiles next, the n-tiles of the
+// super-column fastest.  32 consecutive tiles (what one XCD runs at a time) then form a
+// block of 8 m-tiles x 4 n-tiles (or all m-tiles x more n-tiles for a small expert), which
+// is what bounds the operand traffic that has to come from beyond the XCD's L2.
+constexpr int kSuperN = 4;
+__device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets, int E, int n_tiles, int L,
+                                            int& e_out, int& m0, int& m_lim, int& nt) {
+    int acc = 0;
+    for (int e = 0; e < E; ++e) {
+        const int b = offsets[e], en = offsets[e + 1];
+        const int nm = (en - b + TM - 1) / TM;
+        const int cnt = nm * n_tiles;
+        if (L < acc + cnt) {
+            int local = L - acc;
+            const int full = (n_tiles / kSuperN) * kSuperN * nm;
+            int width = kSuperN, nbase = 0;
+            if (local >= full) {
+                local -= full;
+                nbase = (n_tiles / kSuperN) * kSuperN;
+                width = n_tiles - nbase;
+            } else {
+                const int sc = local / (kSuperN * nm);
+                local -= sc * kSuperN * nm;
+                nbase = sc * kSuperN;
+            }
+            const int m = local / width;
+            nt = nbase + (local - m * width);
+            m0 = b + m * TM;
+            m_lim = en;
+            e_out = e;
+            return true;
+        }
+        acc += cnt;
+    }
+    return false;
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs.  Hand out the logical tile order in
+// blocks of 32 (one block = what the 32 CUs of one XCD run together); consecutive blocks go
+// to different XCDs, so the XCDs work on neighbouring blocks and share panels in the
+// memory-side cache.  gridDim.x is a multiple of 256.
+__device__ __forceinline__ int logical_tile(int wg) {
+    const int xcd = wg & 7, idx = wg >> 3;
+    return (((idx >> 5) * 8 + xcd) << 5) + (idx & 31);
+}
+
+template <int BT, bool DUAL, int EPI>
+__global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;  // 2 x 4 wavefronts, 128 x 64 each
+
+    const int L = logical_tile(blockIdx.x);
+    const int n_out = DUAL ? TN / 2 : TN;  // output columns per tile
+    const int n_tiles = (g.N + n_out - 1) / n_out;
+    int e, m0, m_lim, nt;
+    if (!decode_tile(g.offsets, g.E, n_tiles, L, e, m0, m_lim, nt)) return;
+    const int n0 = nt * n_out;
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = g.K / TK;
+    const int total = nk * g.nseg;
+
+    // ---- per-lane source addressing of the DMA loads (fixed for the whole tile walk) ----
+    // Everything the main loop needs sits in registers: a scalar load inside the loop would
+    // share the LDS reads' wait counter and serialise them.
+    const bf16_t* Aseg[2];
+    const bf16_t* Bseg[2];
+    const bf16_t* B2seg[2];
+#pragma unroll
+    for (int sgi = 0; sgi < 2; ++sgi) {
+        const int q = sgi < g.nseg ? sgi : 0;
+        Aseg[sgi] = static_cast<const bf16_t*>(g.seg[q].A);
+        Bseg[sgi] = static_cast<const bf16_t*>(g.seg[q].B) + (int64_t)e * g.strideB;
+        B2seg[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + (int64_t)e * g.strideB : nullptr;
+    }
+    const int64_t ldb = g.ldb;
+    // A (and B when BT == 1): chunk c = wave*4 + i covers rows 8c .. 8c+7; lane -> row 8c + lane/8, slot lane%8
+    int64_t a_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = (wave * 4 + i) * 8 + (lane >> 3);
+        const int piece = (lane & 7) ^ swz_rows(r);
+        int gr = m0 + r;
+        gr = gr < m_lim ? gr : m_lim - 1;  // rows past the expert's end: any valid row (masked at the store)
+        a_off[i] = (int64_t)gr * g.lda + piece * 8;
+    }
+    int64_t b_off[4];  // element offset of this lane's 16-byte piece inside B (without the k0 part)
+    bool b_second[4] = {false, false, false, false};  // DUAL: piece comes from the second matrix
+    if constexpr (BT == 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = (wave * 4 + i) * 8 + (lane >> 3);
+            const int piece = (lane & 7) ^ swz_rows(r);
+            int gn = n0 + r;
+            gn = gn < g.N ? gn : g.N - 1;
+            b_off[i] = (int64_t)gn * ldb + piece * 8;
+        }
+    } else {
+        // chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int q = (wave * 4 + i) * 2 + (lane >> 5);
+            const int piece = (lane & 31) ^ swz_krow(q);
+            int col;
+            if constexpr (DUAL) col = n0 + (piece & 15) * 8;  // pieces 16..31 come from the second matrix
+            else col = n0 + piece * 8;
+            col = col < g.N ? col : g.N - 8;
+            b_off[i] = (int64_t)q * ldb + col;
+            if constexpr (DUAL) b_second[i] = (piece >> 4) != 0;
+        }
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 4096);
+
+    auto issue = [&](int it, int buf) {
+        const int sg = it >= nk ? 1 : 0;
+        const int k0 = (it - sg * nk) * TK;
+        const uint32_t st = lds_wave + buf * kStageBytes;
+        const bf16_t* A = sg ? Aseg[1] : Aseg[0];
+        const bf16_t* B = sg ? Bseg[1] : Bseg[0];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16(A + a_off[i] + k0, st + i * 1024);
+        if constexpr (BT == 1) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dma16(B + b_off[i] + k0, st + 32768 + i * 1024);
+        } else if constexpr (DUAL) {
+            const bf16_t* B2 = sg ? B2seg[1] : B2seg[0];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                dma16((b_second[i] ? B2 : B) + b_off[i] + (int64_t)k0 * ldb, st + 32768 + i * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dma16(B + b_off[i] + (int64_t)k0 * ldb, st + 32768 + i * 1024);
+        }
+    };
+
+    // ---- per-lane LDS read addressing ----
+    const int l32 = lane & 31, kg = lane >> 5;
+    int a_rd[4];  // byte offset of row (without the piece term)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_rd[i] = (wm * 128 + i * 32 + l32) * 128;
+    const int a_sw = swz_rows(l32);  // the same for all tiles of 32 rows
+    int b_rd[2];                     // B, BT == 1: rows are output columns
+    // B, BT == 0 (transposing reads): lane -> group g16 = lane/16, i16 = lane%16
+    const int g16 = lane >> 4, i16 = lane & 15;
+    const int tr_krow = (g16 >> 1) * 8 + (i16 >> 2);   // + kk*16 + t*4
+    int tr_col[2];                                     // column (elements) inside the 256-wide B tile
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int cb = DUAL ? (j * 128 + wn * 32) : (wn * 64 + j * 32);
+        b_rd[j] = (cb + l32) * 128;
+        tr_col[j] = cb + (g16 & 1) * 16 + (i16 & 3) * 4;
+    }
+
+    // fragments of k-step kk of a stage -> registers
+    auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+        const char* sb = st + 32768;
+        const int piece = kk * 2 + kg;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + ((piece ^ a_sw) << 4));
+        if constexpr (BT == 1) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sb + b_rd[j] + ((piece ^ a_sw) << 4));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                bf16x4 h[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int q = kk * 16 + t * 4 + tr_krow;
+                    const int slot = (tr_col[j] >> 3) ^ swz_krow(q);
+                    const char* p = sb + q * 512 + slot * 16 + (tr_col[j] & 7) * 2;
+                    h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
+                }
+                b[j] = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        }
+    };
+    auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+
+    // ---- main loop: two LDS stages.  The DMA of stage it+2 is issued in the middle of
+    // iteration it (as soon as every wavefront has pulled its last fragments of stage it out
+    // of LDS) and has a whole iteration to land; the MFMAs of the last k-step overlap the
+    // first fragment reads of the next stage.
+    bf16x8 fa[2][4], fb[2][2];
+    // The loop body is branch-free: past the end it re-loads the last k-tile into the free
+    // stage and pulls fragments nobody uses (total >= 1 here: K >= 64).
+    const int last = total - 1;
+    issue(0, 0);
+    issue(last < 1 ? last : 1, 1);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    __syncthreads();
+    load_frags(smem, 0, fa[0], fb[0]);
+
+    for (int it = 0; it < total; ++it) {
+        const char* st = smem + (it & 1) * kStageBytes;
+        const char* nx = smem + ((it + 1) & 1) * kStageBytes;
+        load_frags(st, 1, fa[1], fb[1]);
+        mma(fa[0], fb[0]);
+        load_frags(st, 2, fa[0], fb[0]);
+        mma(fa[1], fb[1]);
+        load_frags(st, 3, fa[1], fb[1]);
+        mma(fa[0], fb[0]);
+        // all of this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        issue(it + 2 < last ? it + 2 : last, it & 1);
+        load_frags(nx, 0, fa[0], fb[0]);
+        mma(fa[1], fb[1]);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus load of the last iteration must not outlive the tile
+
+    // ---- epilogue (accumulator layout: col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4) ----
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+            if (row >= m_lim) continue;
+            if constexpr (DUAL) {
+                const int col = n0 + wn * 32 + l32;
+                if (col < g.N) epilogue_elem<bf16_t, EPI>(g, (int64_t)row * g.ldc + col, acc[i][0][r], acc[i][1][r]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int col = n0 + wn * 64 + j * 32 + l32;
+                    if (col < g.N) epilogue_elem<bf16_t, EPI>(g, (int64_t)row * g.ldc + col, acc[i][j][r], 0.f);
+                }
+            }
+        }
+    }
+}
+
+}  // namespace moe

@@ -248,6 +248,10 @@ __global__ __launch_bounds__(256) void gg_bf16_kernel(const GArgs g) {
         }
 }
 
+}  // namespace moe
+#include "grouped_gemm_bf16.h"
+namespace moe {
+
 // =============================== fp32 FMA path ================================
 // 64x64 tiles, 16x16 threads with 4x4 outputs each, BK = 16; operands addressed
 // with explicit strides so every layout uses the same loader.
@@ -340,6 +344,23 @@ __global__ __launch_bounds__(256) void gg_f32_kernel(const GArgs g, const F32Str
 template <int AT, int BT, bool DUAL, int EPI, bool RAGK>
 static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t st) {
     if (s->dtype == MOE_BF16) {
+        if constexpr (!RAGK && AT == 0) {
+            if (g.K % TK == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8) {
+                auto kern = gg256_kernel<BT, DUAL, EPI>;
+                static bool attr_done = false;  // per instantiation
+                if (!attr_done) {
+                    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+                    attr_done = true;
+                }
+                const int n_out = DUAL ? TN / 2 : TN;
+                const int64_t n_tiles = (g.N + n_out - 1) / n_out;
+                int64_t tiles = ((R + TM - 1) / TM + g.E) * n_tiles;
+                tiles = (tiles + 255) / 256 * 256;
+                kern<<<dim3((unsigned)tiles), 512, kGemmLds, st>>>(g);
+                return;
+            }
+        }
         dim3 grid;
         if (RAGK) grid = dim3((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, g.E);
         else grid = dim3((g.N + BN - 1) / BN, (unsigned)((R + BM - 1) / BM + g.E), 1);
