@@ -2,27 +2,31 @@
 // MFMA 32x32x16 bf16 with fp32 accumulators, operands streamed HBM -> LDS by the
 // DMA path of the global loads (no register staging), double-buffered.
 //
-// The ragged dimension is M (the rows of one expert): forward and dgrad GEMMs of
-// the expert FFN (paper section 3.1; 6*H*H' FLOPs per routed token forward).
+// One template covers the six products of the expert FFN (paper section 3.1;
+// 6*H*H' FLOPs per routed token forward, backward twice that):
 //
-//   A  [rows][K]   K contiguous       (activations: Xp, H, dYp, dA, dB)
-//   B  BT == 0: [K][N]  N contiguous  (forward:  W1, W3 [d][f], W2 [f][d])
-//      BT == 1: [N][K]  K contiguous  (dgrad:    W2 as [f][d], W1/W3 as [d][f])
+//   RAGK == false: the ragged dimension is M (the rows of one expert)
+//       A  [rows][K]  K contiguous                 (Xp, H, dYp, dA, dB)
+//       B  BT == 0: [K][N]  N contiguous           (forward: W1, W3 [d][f], W2 [f][d])
+//          BT == 1: [N][K]  K contiguous           (dgrad:   W2 as [f][d], W1/W3 as [d][f])
+//   RAGK == true: the ragged dimension is the contraction (wgrad), AT == 1, BT == 0
+//       A  [rows][M]  M contiguous                 (Xp, H)
+//       B  [rows][N]  N contiguous                 (dA|dB, dYp)
+//       C_e [M][N] = sum over the rows of expert e;  an expert without rows gets zeros.
 //
-// LDS layout (one 64 KB stage = A tile + B tile, two stages):
-//   A tile: 256 rows x 128 B.  The 16-byte piece p of row r sits in slot p ^ ((r >> 1) & 7),
-//           so the 16 rows a quarter of an MFMA operand read touches cover 256 B of banks once.
-//   B tile, BT == 1: same as A (256 columns of N as rows).
-//   B tile, BT == 0: 64 k-rows x 512 B.  Piece p of k-row q sits in slot
-//           p ^ (2*(q&3) + 8*(q&1)); operands are read with the transposing LDS read
-//           (ds_read_b64_tr_b16), which hands lane i of a 16-lane group column i of
-//           a 4(k) x 16(n) block.
-// A DMA load writes 64 lanes x 16 B to consecutive LDS addresses, so the swizzle
-// is applied on the global side: lane l fetches the piece that belongs in slot l.
+// An operand tile whose contraction index is contiguous in memory ("row form") is
+// kept in LDS as 256 rows x 128 B and read with ds_read_b128; the 16-byte piece p of
+// row r sits in slot p ^ ((r >> 1) & 7).  An operand tile whose other index is contiguous
+// ("k-row form") is kept as 64 k-rows x 512 B and read with the transposing LDS read
+// (ds_read_b64_tr_b16: lane i of a 16-lane group receives column i of a 4(k) x 16 block);
+// piece p of k-row q sits in slot p ^ (2*(q&3) + 8*(q&1)).  Both swizzles make every LDS
+// read instruction of the main loop conflict-free on the 64 banks.  A DMA load writes
+// 64 lanes x 16 B to consecutive LDS addresses, so the swizzle is applied on the global
+// side: lane l fetches the piece that belongs in slot l.
 //
-// DUAL (forward 1): the B tile holds 128 columns of W1 next to the same 128
-// columns of W3; each wavefront accumulates a = x*W1 and b = x*W3 for the same
-// outputs and the epilogue writes silu(a)*b.
+// DUAL: the B tile holds 128 columns of one matrix next to the same 128 columns of a
+// second one (W1|W3 forward, dA|dB wgrad); each wavefront accumulates both products for
+// the same outputs (forward: the epilogue writes silu(a)*b).
 #pragma once
 
 namespace moe {
@@ -33,7 +37,17 @@ constexpr int kGemmLds = 2 * kStageBytes;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 #define LDS_AS __attribute__((address_space(3)))
-#define GLB_AS __attribute__((address_space(1)))
+
+// Scheduling pattern for one k-step: MFMA, LDS read, MFMA, LDS read, ... then a fence.
+template <int N>
+__device__ __forceinline__ void interleave_mfma_dsread() {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 // slot = piece ^ swz: chosen so that the rows one LDS read instruction touches fall into different banks
 __device__ __forceinline__ int swz_rows(int row) { return (row >> 1) & 7; }              // 128-byte rows, b128 reads
@@ -48,12 +62,28 @@ __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_addr) {
                  : "memory", "m0");
 }
 
-// Logical tile id -> (expert, m-tile, n-tile).  Order: expert-major; inside an expert the
-// n-tiles are walked in super-columns of kSuperN, m-tiles next, the n-tiles of the
-// super-column fastest.  32 consecutive tiles (what one XCD runs at a time) then form a
-// block of 8 m-tiles x 4 n-tiles (or all m-tiles x more n-tiles for a small expert), which
-// is what bounds the operand traffic that has to come from beyond the XCD's L2.
+// Walk of the n-tiles x m-tiles grid of one expert: n-tiles in super-columns of kSuperN,
+// m-tiles next, the n-tiles of the super-column fastest.  32 consecutive tiles (what one
+// XCD runs at a time) then form a block of 8 m-tiles x 4 n-tiles (or all m-tiles x more
+// n-tiles for a short expert), which bounds the operand traffic from beyond the XCD's L2.
 constexpr int kSuperN = 4;
+__device__ __forceinline__ void walk_tile(int local, int nm, int n_tiles, int& m, int& nt) {
+    const int full = (n_tiles / kSuperN) * kSuperN * nm;
+    int width = kSuperN, nbase = 0;
+    if (local >= full) {
+        local -= full;
+        nbase = (n_tiles / kSuperN) * kSuperN;
+        width = n_tiles - nbase;
+    } else {
+        const int sc = local / (kSuperN * nm);
+        local -= sc * kSuperN * nm;
+        nbase = sc * kSuperN;
+    }
+    m = local / width;
+    nt = nbase + (local - m * width);
+}
+
+// Logical tile id -> (expert, first row, row limit, n-tile) when M is ragged: expert-major.
 __device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets, int E, int n_tiles, int L,
                                             int& e_out, int& m0, int& m_lim, int& nt) {
     int acc = 0;
@@ -62,20 +92,8 @@ __device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets,
         const int nm = (en - b + TM - 1) / TM;
         const int cnt = nm * n_tiles;
         if (L < acc + cnt) {
-            int local = L - acc;
-            const int full = (n_tiles / kSuperN) * kSuperN * nm;
-            int width = kSuperN, nbase = 0;
-            if (local >= full) {
-                local -= full;
-                nbase = (n_tiles / kSuperN) * kSuperN;
-                width = n_tiles - nbase;
-            } else {
-                const int sc = local / (kSuperN * nm);
-                local -= sc * kSuperN * nm;
-                nbase = sc * kSuperN;
-            }
-            const int m = local / width;
-            nt = nbase + (local - m * width);
+            int m;
+            walk_tile(L - acc, nm, n_tiles, m, nt);
             m0 = b + m * TM;
             m_lim = en;
             e_out = e;
@@ -95,8 +113,9 @@ __device__ __forceinline__ int logical_tile(int wg) {
     return (((idx >> 5) * 8 + xcd) << 5) + (idx & 31);
 }
 
-template <int BT, bool DUAL, int EPI>
+template <int AT, int BT, bool DUAL, int EPI, bool RAGK>
 __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
+    static_assert(RAGK ? (AT == 1 && BT == 0) : (AT == 0), "operand forms");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 2, wn = wave & 3;  // 2 x 4 wavefronts, 128 x 64 each
@@ -104,8 +123,24 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
     const int L = logical_tile(blockIdx.x);
     const int n_out = DUAL ? TN / 2 : TN;  // output columns per tile
     const int n_tiles = (g.N + n_out - 1) / n_out;
-    int e, m0, m_lim, nt;
-    if (!decode_tile(g.offsets, g.E, n_tiles, L, e, m0, m_lim, nt)) return;
+    int e, m0, m_lim, nt, kbeg, kend;
+    if constexpr (RAGK) {
+        const int m_tiles = (g.M + TM - 1) / TM;
+        const int per = m_tiles * n_tiles;
+        const int oi = L / per;
+        if (oi >= g.E) return;
+        e = g.order ? g.order[oi] : oi;  // heaviest experts first
+        int m;
+        walk_tile(L - oi * per, m_tiles, n_tiles, m, nt);
+        m0 = m * TM;
+        m_lim = g.M;
+        kbeg = g.offsets[e];
+        kend = g.offsets[e + 1];
+    } else {
+        if (!decode_tile(g.offsets, g.E, n_tiles, L, e, m0, m_lim, nt)) return;
+        kbeg = 0;
+        kend = g.K;
+    }
     const int n0 = nt * n_out;
 
     f32x16 acc[4][2];
@@ -116,184 +151,255 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nk = g.K / TK;
+    const int nk = (kend - kbeg + TK - 1) / TK;  // exact when M is ragged (K % 64 == 0)
     const int total = nk * g.nseg;
 
-    // ---- per-lane source addressing of the DMA loads (fixed for the whole tile walk) ----
-    // Everything the main loop needs sits in registers: a scalar load inside the loop would
-    // share the LDS reads' wait counter and serialise them.
-    const bf16_t* Aseg[2];
-    const bf16_t* Bseg[2];
-    const bf16_t* B2seg[2];
+    if (total > 0) {
+        // ---- per-lane source addressing of the DMA loads (fixed for the whole tile walk) ----
+        // Everything the main loop needs sits in registers: a scalar load inside the loop would
+        // share the LDS reads' wait counter and serialise them.
+        const bf16_t* Aseg[2];
+        const bf16_t* Bseg[2];
+        const bf16_t* B2seg[2];
 #pragma unroll
-    for (int sgi = 0; sgi < 2; ++sgi) {
-        const int q = sgi < g.nseg ? sgi : 0;
-        Aseg[sgi] = static_cast<const bf16_t*>(g.seg[q].A);
-        Bseg[sgi] = static_cast<const bf16_t*>(g.seg[q].B) + (int64_t)e * g.strideB;
-        B2seg[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + (int64_t)e * g.strideB : nullptr;
-    }
-    const int64_t ldb = g.ldb;
-    // A (and B when BT == 1): chunk c = wave*4 + i covers rows 8c .. 8c+7; lane -> row 8c + lane/8, slot lane%8
-    int64_t a_off[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = (wave * 4 + i) * 8 + (lane >> 3);
-        const int piece = (lane & 7) ^ swz_rows(r);
-        int gr = m0 + r;
-        gr = gr < m_lim ? gr : m_lim - 1;  // rows past the expert's end: any valid row (masked at the store)
-        a_off[i] = (int64_t)gr * g.lda + piece * 8;
-    }
-    int64_t b_off[4];  // element offset of this lane's 16-byte piece inside B (without the k0 part)
-    bool b_second[4] = {false, false, false, false};  // DUAL: piece comes from the second matrix
-    if constexpr (BT == 1) {
+        for (int sgi = 0; sgi < 2; ++sgi) {
+            const int q = sgi < g.nseg ? sgi : 0;
+            const int64_t eoff = RAGK ? 0 : (int64_t)e * g.strideB;
+            Aseg[sgi] = static_cast<const bf16_t*>(g.seg[q].A);
+            Bseg[sgi] = static_cast<const bf16_t*>(g.seg[q].B) + eoff;
+            B2seg[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;
+        }
+        const int64_t lda = g.lda, ldb = g.ldb;
+        // row form: chunk c = wave*4 + i covers rows 8c .. 8c+7; lane -> row 8c + lane/8, slot lane%8
+        // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
+        int64_t a_off[4], b_off[4];  // element offsets of this lane's 16-byte pieces (k-independent part)
+        int a_q[4], b_q[4];          // k-row form: the k-row inside the stage
+        bool b_second[4] = {false, false, false, false};  // DUAL: piece comes from the second matrix
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = (wave * 4 + i) * 8 + (lane >> 3);
-            const int piece = (lane & 7) ^ swz_rows(r);
-            int gn = n0 + r;
-            gn = gn < g.N ? gn : g.N - 1;
-            b_off[i] = (int64_t)gn * ldb + piece * 8;
-        }
-    } else {
-        // chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int q = (wave * 4 + i) * 2 + (lane >> 5);
-            const int piece = (lane & 31) ^ swz_krow(q);
-            int col;
-            if constexpr (DUAL) col = n0 + (piece & 15) * 8;  // pieces 16..31 come from the second matrix
-            else col = n0 + piece * 8;
-            col = col < g.N ? col : g.N - 8;
-            b_off[i] = (int64_t)q * ldb + col;
-            if constexpr (DUAL) b_second[i] = (piece >> 4) != 0;
-        }
-    }
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
-    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 4096);
-
-    auto issue = [&](int it, int buf) {
-        const int sg = it >= nk ? 1 : 0;
-        const int k0 = (it - sg * nk) * TK;
-        const uint32_t st = lds_wave + buf * kStageBytes;
-        const bf16_t* A = sg ? Aseg[1] : Aseg[0];
-        const bf16_t* B = sg ? Bseg[1] : Bseg[0];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) dma16(A + a_off[i] + k0, st + i * 1024);
-        if constexpr (BT == 1) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(B + b_off[i] + k0, st + 32768 + i * 1024);
-        } else if constexpr (DUAL) {
-            const bf16_t* B2 = sg ? B2seg[1] : B2seg[0];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                dma16((b_second[i] ? B2 : B) + b_off[i] + (int64_t)k0 * ldb, st + 32768 + i * 1024);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(B + b_off[i] + (int64_t)k0 * ldb, st + 32768 + i * 1024);
-        }
-    };
-
-    // ---- per-lane LDS read addressing ----
-    const int l32 = lane & 31, kg = lane >> 5;
-    int a_rd[4];  // byte offset of row (without the piece term)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a_rd[i] = (wm * 128 + i * 32 + l32) * 128;
-    const int a_sw = swz_rows(l32);  // the same for all tiles of 32 rows
-    int b_rd[2];                     // B, BT == 1: rows are output columns
-    // B, BT == 0 (transposing reads): lane -> group g16 = lane/16, i16 = lane%16
-    const int g16 = lane >> 4, i16 = lane & 15;
-    const int tr_krow = (g16 >> 1) * 8 + (i16 >> 2);   // + kk*16 + t*4
-    int tr_col[2];                                     // column (elements) inside the 256-wide B tile
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int cb = DUAL ? (j * 128 + wn * 32) : (wn * 64 + j * 32);
-        b_rd[j] = (cb + l32) * 128;
-        tr_col[j] = cb + (g16 & 1) * 16 + (i16 & 3) * 4;
-    }
-
-    // fragments of k-step kk of a stage -> registers
-    auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
-        const char* sb = st + 32768;
-        const int piece = kk * 2 + kg;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + ((piece ^ a_sw) << 4));
-        if constexpr (BT == 1) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sb + b_rd[j] + ((piece ^ a_sw) << 4));
-        } else {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                bf16x4 h[2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int q = kk * 16 + t * 4 + tr_krow;
-                    const int slot = (tr_col[j] >> 3) ^ swz_krow(q);
-                    const char* p = sb + q * 512 + slot * 16 + (tr_col[j] & 7) * 2;
-                    h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
-                }
-                b[j] = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
+            const int c = wave * 4 + i;
+            if constexpr (AT == 0) {
+                const int r = c * 8 + (lane >> 3);
+                int gr = m0 + r;
+                gr = gr < m_lim ? gr : m_lim - 1;  // rows past the expert's end: any valid row (masked at the store)
+                a_off[i] = (int64_t)gr * lda + ((lane & 7) ^ swz_rows(r)) * 8;
+                a_q[i] = 0;
+            } else {
+                a_q[i] = c * 2 + (lane >> 5);
+                int col = m0 + ((lane & 31) ^ swz_krow(a_q[i])) * 8;
+                col = col < g.M ? col : g.M - 8;
+                a_off[i] = col;
+            }
+            if constexpr (BT == 1) {
+                const int r = c * 8 + (lane >> 3);
+                int gn = n0 + r;
+                gn = gn < g.N ? gn : g.N - 1;
+                b_off[i] = (int64_t)gn * ldb + ((lane & 7) ^ swz_rows(r)) * 8;
+                b_q[i] = 0;
+            } else {
+                b_q[i] = c * 2 + (lane >> 5);
+                const int piece = (lane & 31) ^ swz_krow(b_q[i]);
+                int col;
+                if constexpr (DUAL) col = n0 + (piece & 15) * 8;  // pieces 16..31 come from the second matrix
+                else col = n0 + piece * 8;
+                col = col < g.N ? col : g.N - 8;
+                b_off[i] = col;
+                if constexpr (DUAL) b_second[i] = (piece >> 4) != 0;
             }
         }
-    };
-    auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    };
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
+        const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 4096);
 
-    // ---- main loop: two LDS stages.  The DMA of stage it+2 is issued in the middle of
-    // iteration it (as soon as every wavefront has pulled its last fragments of stage it out
-    // of LDS) and has a whole iteration to land; the MFMAs of the last k-step overlap the
-    // first fragment reads of the next stage.
-    bf16x8 fa[2][4], fb[2][2];
-    // The loop body is branch-free: past the end it re-loads the last k-tile into the free
-    // stage and pulls fragments nobody uses (total >= 1 here: K >= 64).
-    const int last = total - 1;
-    issue(0, 0);
-    issue(last < 1 ? last : 1, 1);
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    __syncthreads();
-    load_frags(smem, 0, fa[0], fb[0]);
+        auto issue = [&](int it, int buf) {
+            const int sg = it >= nk ? 1 : 0;
+            const int k0 = kbeg + (it - sg * nk) * TK;
+            const uint32_t st = lds_wave + buf * kStageBytes;
+            const bf16_t* A = sg ? Aseg[1] : Aseg[0];
+            const bf16_t* B = sg ? Bseg[1] : Bseg[0];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (AT == 0) {
+                    dma16(A + a_off[i] + k0, st + i * 1024);
+                } else {
+                    int kr = k0 + a_q[i];
+                    kr = kr < kend ? kr : kend - 1;  // past the expert's rows: a valid row; zeroed in LDS below
+                    dma16(A + (int64_t)kr * lda + a_off[i], st + i * 1024);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (BT == 1) {
+                    dma16(B + b_off[i] + k0, st + 32768 + i * 1024);
+                } else {
+                    int kr = k0 + b_q[i];
+                    if constexpr (RAGK) kr = kr < kend ? kr : kend - 1;
+                    const bf16_t* src = B;
+                    if constexpr (DUAL) src = b_second[i] ? (sg ? B2seg[1] : B2seg[0]) : B;
+                    dma16(src + (int64_t)kr * ldb + b_off[i], st + 32768 + i * 1024);
+                }
+            }
+        };
 
-    for (int it = 0; it < total; ++it) {
-        const char* st = smem + (it & 1) * kStageBytes;
-        const char* nx = smem + ((it + 1) & 1) * kStageBytes;
-        load_frags(st, 1, fa[1], fb[1]);
-        mma(fa[0], fb[0]);
-        load_frags(st, 2, fa[0], fb[0]);
-        mma(fa[1], fb[1]);
-        load_frags(st, 3, fa[1], fb[1]);
-        mma(fa[0], fb[0]);
-        // all of this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        // ---- per-lane LDS read addressing ----
+        const int l32 = lane & 31, kg = lane >> 5;
+        const int a_sw = swz_rows(l32);  // the same for all tiles of 32 rows
+        // k-row form (transposing reads): lane -> group g16 = lane/16, i16 = lane%16
+        const int g16 = lane >> 4, i16 = lane & 15;
+        const int tr_krow = (g16 >> 1) * 8 + (i16 >> 2);  // + kk*16 + t*4
+        const int tr_sw = swz_krow(tr_krow);              // kk*16 + t*4 do not change the swizzle
+        const int tr_lane_col = (g16 & 1) * 16 + (i16 & 3) * 4;
+        int a_rd[4], b_rd[2];  // byte offsets inside the operand tile, without the k-step term
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (AT == 0) {
+                a_rd[i] = (wm * 128 + i * 32 + l32) * 128;
+            } else {
+                const int col = wm * 128 + i * 32 + tr_lane_col;
+                a_rd[i] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int cb = DUAL ? (j * 128 + wn * 32) : (wn * 64 + j * 32);
+            if constexpr (BT == 1) {
+                b_rd[j] = (cb + l32) * 128;
+            } else {
+                const int col = cb + tr_lane_col;
+                b_rd[j] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
+            }
+        }
+
+        // fragments of k-step kk of a stage -> registers
+        auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+            const char* sb = st + 32768;
+            const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (AT == 0) {
+                    a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + rowform);
+                } else {
+                    const char* p = st + a_rd[i] + kk * 8192;
+                    const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
+                    const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
+                    a[i] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if constexpr (BT == 1) {
+                    b[j] = *reinterpret_cast<const bf16x8*>(sb + b_rd[j] + rowform);
+                } else {
+                    const char* p = sb + b_rd[j] + kk * 8192;
+                    const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
+                    const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
+                    b[j] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+        };
+        auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        };
+        constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? 2 : 4);
+
+        // Ragged K: the k-rows of the last stage that lie past the expert's rows are zeroed in the
+        // A tile (the B tile holds a valid, finite row there).  Each lane overwrites exactly the
+        // 16 bytes its own DMA loads delivered, after it has waited for them: no other wavefront
+        // writes those bytes.
+        auto zero_tail = [&](int it, char* st) {
+            if constexpr (RAGK) {
+                const int k0 = kbeg + it * TK;
+                if (k0 + TK > kend) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (k0 + a_q[i] >= kend)
+                            *reinterpret_cast<u32x4*>(st + (wave * 4 + i) * 1024 + lane * 16) = (u32x4){0, 0, 0, 0};
+                }
+            }
+        };
+
+        // ---- main loop: two LDS stages.  The DMA of stage it+2 is issued in the middle of
+        // iteration it (as soon as every wavefront has pulled its last fragments of stage it out
+        // of LDS) and has a whole iteration to land; the MFMAs of the last k-step overlap the
+        // first fragment reads of the next stage.  The loop body is branch-free: past the end
+        // it re-loads the last k-tile into the free stage and pulls fragments nobody uses.
+        bf16x8 fa[2][4], fb[2][2];
+        const int last = total - 1;
+        issue(0, 0);
+        issue(last < 1 ? last : 1, 1);
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        zero_tail(0, smem);
         __syncthreads();
-        issue(it + 2 < last ? it + 2 : last, it & 1);
-        load_frags(nx, 0, fa[0], fb[0]);
-        mma(fa[1], fb[1]);
+        load_frags(smem, 0, fa[0], fb[0]);
+
+        for (int it = 0; it < total; ++it) {
+            const char* st = smem + (it & 1) * kStageBytes;
+            char* nx = smem + ((it + 1) & 1) * kStageBytes;
+            // k-step kk: its 8 MFMAs are interleaved one-to-one with the LDS reads of k-step kk+1
+            load_frags(st, 1, fa[1], fb[1]);
+            mma(fa[0], fb[0]);
+            interleave_mfma_dsread<kReads>();
+            load_frags(st, 2, fa[0], fb[0]);
+            mma(fa[1], fb[1]);
+            interleave_mfma_dsread<kReads>();
+            load_frags(st, 3, fa[1], fb[1]);
+            mma(fa[0], fb[0]);
+            interleave_mfma_dsread<kReads>();
+            // all of this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            if constexpr (RAGK) {
+                if (it + 1 <= last) zero_tail(it + 1, nx);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            __syncthreads();
+            issue(it + 2 < last ? it + 2 : last, it & 1);
+            load_frags(nx, 0, fa[0], fb[0]);
+            mma(fa[1], fb[1]);
+            interleave_mfma_dsread<kReads>();
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus load of the last iteration must not outlive the tile
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus load of the last iteration must not outlive the tile
 
     // ---- epilogue (accumulator layout: col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4) ----
+    const int64_t cbase = RAGK ? (int64_t)e * g.strideC : 0;
+    const int l32e = lane & 31, kge = lane >> 5;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+            const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
             if (row >= m_lim) continue;
             if constexpr (DUAL) {
-                const int col = n0 + wn * 32 + l32;
-                if (col < g.N) epilogue_elem<bf16_t, EPI>(g, (int64_t)row * g.ldc + col, acc[i][0][r], acc[i][1][r]);
+                const int col = n0 + wn * 32 + l32e;
+                if (col < g.N)
+                    epilogue_elem<bf16_t, EPI>(g, cbase + (int64_t)row * g.ldc + col, acc[i][0][r], acc[i][1][r]);
             } else {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const int col = n0 + wn * 64 + j * 32 + l32;
-                    if (col < g.N) epilogue_elem<bf16_t, EPI>(g, (int64_t)row * g.ldc + col, acc[i][j][r], 0.f);
+                    const int col = n0 + wn * 64 + j * 32 + l32e;
+                    if (col < g.N) epilogue_elem<bf16_t, EPI>(g, cbase + (int64_t)row * g.ldc + col, acc[i][j][r], 0.f);
                 }
             }
         }
     }
+}
+
+// Experts sorted by row count, heaviest first (one workgroup; E <= 256): the wgrad tiles of a
+// heavy expert take longest, so they are started first.
+__global__ __launch_bounds__(256) void expert_order_kernel(const int32_t* __restrict__ offsets, int E,
+                                                           int32_t* __restrict__ order) {
+    const int e = threadIdx.x;
+    if (e >= E) return;
+    const int mine = offsets[e + 1] - offsets[e];
+    int rank = 0;
+    for (int j = 0; j < E; ++j) {
+        const int c = offsets[j + 1] - offsets[j];
+        rank += (c > mine) || (c == mine && j < e);
+    }
+    order[rank] = e;
 }
 
 }  // namespace moe

@@ -51,6 +51,7 @@ struct GArgs {
     const void* S0;        // saved A (EPI_DH: read; EPI_SWIGLU: written if non-null)
     const void* S1;        // saved B
     int64_t ldc;
+    const int32_t* order;  // ragged K: experts by row count, heaviest first (may be null)
 };
 
 template <class T, int EPI>
@@ -344,9 +345,12 @@ __global__ __launch_bounds__(256) void gg_f32_kernel(const GArgs g, const F32Str
 template <int AT, int BT, bool DUAL, int EPI, bool RAGK>
 static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t st) {
     if (s->dtype == MOE_BF16) {
-        if constexpr (!RAGK && AT == 0) {
-            if (g.K % TK == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8) {
-                auto kern = gg256_kernel<BT, DUAL, EPI>;
+        constexpr bool fast_form = RAGK ? (AT == 1 && BT == 0) : (AT == 0);
+        if constexpr (fast_form) {
+            const bool ok = g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8 &&
+                            (RAGK ? (g.M >= 8) : (g.K % TK == 0));
+            if (ok) {
+                auto kern = gg256_kernel<AT, BT, DUAL, EPI, RAGK>;
                 static bool attr_done = false;  // per instantiation
                 if (!attr_done) {
                     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -355,7 +359,9 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
                 }
                 const int n_out = DUAL ? TN / 2 : TN;
                 const int64_t n_tiles = (g.N + n_out - 1) / n_out;
-                int64_t tiles = ((R + TM - 1) / TM + g.E) * n_tiles;
+                int64_t tiles;
+                if (RAGK) tiles = (int64_t)g.E * ((g.M + TM - 1) / TM) * n_tiles;
+                else tiles = ((R + TM - 1) / TM + g.E) * n_tiles;
                 tiles = (tiles + 255) / 256 * 256;
                 kern<<<dim3((unsigned)tiles), 512, kGemmLds, st>>>(g);
                 return;
@@ -382,7 +388,7 @@ size_t ffn_fwd_workspace_bytes(const moe_shape* s) {
     return align_up((size_t)s->T * s->k * s->f * el_size(s), 256);  // H
 }
 size_t ffn_bwd_workspace_bytes(const moe_shape* s) {
-    return 5 * align_up((size_t)s->T * s->k * s->f * el_size(s), 256);  // H, dA, dB, (A, B when recomputing)
+    return 5 * align_up((size_t)s->T * s->k * s->f * el_size(s), 256) + 1024;  // H, dA, dB, (A, B when recomputing), expert order
 }
 
 }  // namespace moe
@@ -464,6 +470,8 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     void* H = cv.take(rf);
     void* dA = cv.take(rf);
     void* dB = cv.take(rf);
+    int32_t* order = static_cast<int32_t*>(cv.take(1024));
+    expert_order_kernel<<<1, 256, 0, st>>>(offsets, s->E, order);
     if (!a_save || !b_save) {  // expert-only recomputation: rebuild A and B (H is rewritten below anyway)
         void* A = cv.take(rf);
         void* B = cv.take(rf);
@@ -493,7 +501,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
         g.offsets = offsets; g.E = s->E; g.M = s->f; g.N = s->d; g.nseg = 1;
         g.seg[0] = {H, dy_perm, nullptr};
         g.lda = s->f; g.ldb = s->d; g.strideC = (int64_t)s->f * s->d;
-        g.C0 = dw2; g.ldc = s->d;
+        g.C0 = dw2; g.ldc = s->d; g.order = order;
         launch_gg<1, 0, false, EPI_STORE, true>(s, g, R, st);
     }
     {  // [dW1|dW3][e] = Xp_e^T * [dA_e|dB_e]
@@ -501,7 +509,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
         g.offsets = offsets; g.E = s->E; g.M = s->d; g.N = s->f; g.nseg = 1;
         g.seg[0] = {x_perm, dA, dB};
         g.lda = s->d; g.ldb = s->f; g.strideC = (int64_t)s->d * s->f;
-        g.C0 = dw1; g.C1 = dw3; g.ldc = s->f;
+        g.C0 = dw1; g.C1 = dw3; g.ldc = s->f; g.order = order;
         launch_gg<1, 0, true, EPI_STORE2, true>(s, g, R, st);
     }
     return launch_status(who);

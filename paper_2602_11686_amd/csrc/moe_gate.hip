@@ -14,7 +14,7 @@ constexpr int kGateTokens = 16;   // tokens per workgroup
 constexpr int kGateKC = 256;      // hidden-dimension chunk staged in LDS
 constexpr int kGateMaxNE = MOE_MAX_EXPERTS / 64;
 
-size_t gate_workspace_bytes(const moe_shape*) { return 256; }
+size_t gate_workspace_bytes(const moe_shape* s) { return align_up((size_t)MOE_MAX_EXPERTS * s->d * 2, 256); }
 
 // One workgroup = 4 wavefronts = 16 tokens; wave w owns tokens w, w+4, w+8, w+12
 // of the block, lane l owns experts l, l+64, ...
@@ -106,6 +106,136 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(const T* __restrict__ x,
         for (int s = 0; s < k; ++s) z += __expf(sel[wave][s] - m0);
         for (int s = lane; s < k; s += 64) wout[(size_t)t * k + s] = __expf(sel[wave][s] - m0) / z;
         __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---- bf16 forward on the matrix cores ------------------------------------------------------
+// One workgroup = 32 tokens, 4 wavefronts; wavefront w contracts the quarter
+// [w*d/4, (w+1)*d/4) of the hidden dimension for all 32 tokens and all experts with MFMA
+// 32x32x16 (operands straight from global memory: a lane reads 64 contiguous bytes of its
+// token row / of its expert's row of the transposed gate weight per 64-wide k chunk), the
+// four partial sums meet in LDS and are added in a fixed order, then each wavefront runs
+// the top-k of 8 tokens.
+typedef __bf16 gbf16x8 __attribute__((ext_vector_type(8)));
+typedef float gf32x16 __attribute__((ext_vector_type(16)));
+constexpr int kGateMT = 32;
+
+__global__ void gate_transpose_bf16_kernel(const bf16_t* __restrict__ wg, bf16_t* __restrict__ wgT, int d, int E,
+                                           int Epad) {
+    const int64_t n = (int64_t)d * Epad;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int e = (int)(i / d), c = (int)(i - (int64_t)e * d);
+        wgT[i] = e < E ? wg[(size_t)c * E + e] : (bf16_t)0;
+    }
+}
+
+__device__ __forceinline__ void topk_softmax_token(float (&v)[kGateMaxNE], int lane, int k, float* sel,
+                                                   int32_t* ids_t, float* w_t) {
+    for (int s = 0; s < k; ++s) {
+        float bv = v[0];
+        int be = lane;
+#pragma unroll
+        for (int j = 1; j < kGateMaxNE; ++j)
+            if (v[j] > bv) { bv = v[j]; be = lane + 64 * j; }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const float ov = __shfl_xor(bv, m, 64);
+            const int oe = __shfl_xor(be, m, 64);
+            if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+        }
+        if ((be & 63) == lane) {
+#pragma unroll
+            for (int j = 0; j < kGateMaxNE; ++j)
+                if (be == lane + 64 * j) v[j] = -INFINITY;
+        }
+        if (lane == 0) {
+            ids_t[s] = be;
+            sel[s] = bv;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const float m0 = sel[0];
+    float z = 0.f;
+    for (int s = 0; s < k; ++s) z += __expf(sel[s] - m0);
+    for (int s = lane; s < k; s += 64) w_t[s] = __expf(sel[s] - m0) / z;
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int NT>  // expert tiles of 32
+__global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wgT,
+                                                             const float* __restrict__ bias, int32_t* __restrict__ ids,
+                                                             float* __restrict__ wout, float* __restrict__ logits_out,
+                                                             int Tn, int d, int E, int k) {
+    extern __shared__ float part[];  // [4][32][NT*32] partial logits, then sel[4][MOE_MAX_EXPERTS]
+    constexpr int EP = NT * 32;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int t0 = blockIdx.x * kGateMT;
+    int trow = t0 + l32;
+    trow = trow < Tn ? trow : Tn - 1;
+    const int kq = d / 4;
+    const bf16_t* xa = x + (size_t)trow * d + wave * kq + kg * 32;
+    const bf16_t* wb = wgT + (size_t)l32 * d + wave * kq + kg * 32;
+
+    gf32x16 acc[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    for (int c = 0; c < kq; c += 64) {
+        gbf16x8 a[4];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) a[s4] = *reinterpret_cast<const gbf16x8*>(xa + c + s4 * 8);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            gbf16x8 b[4];
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4)
+                b[s4] = *reinterpret_cast<const gbf16x8*>(wb + (size_t)j * 32 * d + c + s4 * 8);
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s4], b[s4], acc[j], 0, 0, 0);
+        }
+    }
+    // partial sums -> LDS (accumulator layout: col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4)
+    float* mine = part + (size_t)wave * kGateMT * EP;
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = (r >> 2) * 8 + kg * 4 + (r & 3);
+            mine[row * EP + j * 32 + l32] = acc[j][r];
+        }
+    __syncthreads();
+    // wave w finishes tokens 8w .. 8w+7; lane owns experts lane, lane+64, ...
+    float vals[8][kGateMaxNE];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = wave * 8 + i;
+#pragma unroll
+        for (int j = 0; j < kGateMaxNE; ++j) {
+            const int e = lane + 64 * j;
+            float v = -INFINITY;
+            if (e < E) {
+                v = ((part[(0 * kGateMT + row) * EP + e] + part[(1 * kGateMT + row) * EP + e]) +
+                     part[(2 * kGateMT + row) * EP + e]) + part[(3 * kGateMT + row) * EP + e];
+                v += bias ? bias[e] : 0.f;
+            }
+            vals[i][j] = v;
+        }
+    }
+    __syncthreads();  // partial sums consumed; LDS is reused for the picked logits
+    float* sel = part + wave * MOE_MAX_EXPERTS;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int t = t0 + wave * 8 + i;
+        if (t >= Tn) continue;
+        if (logits_out)
+#pragma unroll
+            for (int j = 0; j < kGateMaxNE; ++j)
+                if (lane + 64 * j < E) logits_out[(size_t)t * E + lane + 64 * j] = vals[i][j];
+        topk_softmax_token(vals[i], lane, k, sel, ids + (size_t)t * k, wout + (size_t)t * k);
     }
 }
 
@@ -218,9 +348,35 @@ extern "C" moe_status moe_gate_topk(const moe_shape* s, const void* x, const voi
     MOE_RETURN_IF(check_ptr(topk_ids, "topk_ids", who));
     MOE_RETURN_IF(check_ptr(topk_w, "topk_w", who));
     MOE_RETURN_IF(check_ptr(logits_out, "logits_out", who, true));
-    (void)ws;
-    (void)ws_bytes;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (s->dtype == MOE_BF16 && s->d % 256 == 0) {
+        MOE_RETURN_IF(check_ptr(ws, "ws", who));
+        if (ws_bytes < gate_workspace_bytes(s)) {
+            set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, gate_workspace_bytes(s));
+            return MOE_ERR_WORKSPACE_TOO_SMALL;
+        }
+        const int nt = (s->E + 31) / 32;
+        const int NT = nt <= 1 ? 1 : nt <= 2 ? 2 : nt <= 4 ? 4 : 8;
+        bf16_t* wgT = static_cast<bf16_t*>(ws);
+        gate_transpose_bf16_kernel<<<256, 256, 0, st>>>(static_cast<const bf16_t*>(w_gate), wgT, s->d, s->E, NT * 32);
+        const int grid = (s->T + kGateMT - 1) / kGateMT;
+        const size_t lds = (size_t)4 * kGateMT * NT * 32 * sizeof(float) < (size_t)4 * MOE_MAX_EXPERTS * 4
+                               ? (size_t)4 * MOE_MAX_EXPERTS * 4 : (size_t)4 * kGateMT * NT * 32 * sizeof(float);
+#define MOE_GATE_LAUNCH(N)                                                                                         \
+    {                                                                                                              \
+        static bool attr = false;                                                                                  \
+        if (!attr) {                                                                                               \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_topk_mfma_kernel<N>),                    \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGateMT * 256 * 4);          \
+            attr = true;                                                                                           \
+        }                                                                                                          \
+        gate_topk_mfma_kernel<N><<<grid, 256, lds, st>>>(static_cast<const bf16_t*>(x), wgT, bias, topk_ids, topk_w, \
+                                                         logits_out, s->T, s->d, s->E, s->k);                      \
+    }
+        if (NT == 1) MOE_GATE_LAUNCH(1) else if (NT == 2) MOE_GATE_LAUNCH(2) else if (NT == 4) MOE_GATE_LAUNCH(4) else MOE_GATE_LAUNCH(8)
+#undef MOE_GATE_LAUNCH
+        return launch_status(who);
+    }
     const int grid = (s->T + kGateTokens - 1) / kGateTokens;
     if (s->dtype == MOE_BF16)
         gate_topk_kernel<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(x),
