@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2_e64k4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the hot path of one device's token share); "
@@ -75,6 +77,15 @@ def main():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     B.lib()  # fail loudly if the HIP library is not built
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "repeats": 5}))
+        return
 
     w = I.WORKLOADS[args.workload]
     dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
@@ -140,6 +151,12 @@ def main():
         stages["permute_bwd"]["gbs"] = round(comb_bytes / (stage_ms["permute_bwd"] * 1e-3) / 1e9, 1)
         stages["combine_bwd"]["gbs"] = round(((1 + 2 * w.k) * w.T * w.d * el) / (stage_ms["combine_bwd"] * 1e-3) / 1e9, 1)
 
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):  # HBM bytes of the grouped-FFN kernels measured with rocprofv3 --pmc (see profiles/)
+        with open(tpath) as fh:
+            traffic = json.load(fh).get(w.name, {}).get("ffn_hbm_bytes_per_step")
+
     out = {
         "metric": "MoE-layer tokens/s; grouped-GEMM bf16 TFLOP/s and % MFMA peak, 1 GPU",
         "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -150,7 +167,7 @@ def main():
                    "max_over_mean_load": float(counts.max() / counts.mean()),
                    "empty_experts": int((counts == 0).sum())},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "kernel": "grouped FFN (moe_grouped_ffn_fwd" + ("+bwd" if w.backward else "") + ")",
                      "flops_per_launch": flops, "ms_per_launch": ffn_ms},
         "stages": stages,
