@@ -1,0 +1,230 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The oracle cannot run a whole Mixtral-sized layer in a test, so at full size
+  * the gate and the permutation are compared in full (integer outputs bit-exact),
+  * the float stages are compared on samples the oracle computes exactly: whole rows of
+    Yp / dXp (a row depends on its own input row only), whole tokens of Y / dX, and for the
+    weight gradients a subset J of the intermediate channels over ALL rows (restricting W1, W3 to
+    columns J and W2 to rows J is itself an FFN whose gradients are the J-slices of the full ones),
+  * linear stages that need a full upstream tensor (combine, combine backward, gate backward)
+    are fed a seeded random stand-in for it on both sides.
+Samples always include the first and last row of every expert and every expert smaller than a tile.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2602_11686_amd import binding as B
+from paper_2602_11686_amd import inputs as I
+from paper_2602_11686_amd.layer import MoeLayerBuffers
+from gpu_common import TOL, check_gate, dev, host, shape_of, tdtype
+from helpers import rel_max
+
+pytestmark = pytest.mark.gpu
+
+WORKLOADS = ["cfg1_tiny_f32", "cfg2_e64k4", "cfg3_mixtral", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced"]
+
+
+class Case:
+    def __init__(self, name):
+        self.w = w = I.WORKLOADS[name]
+        self.s = shape_of(w)
+        print(f"[full-size] {name}: generating inputs", flush=True)
+        self.inp = I.layer_inputs(w)
+        self.g = {n: (dev(v, w) if n != "bias" else torch.from_numpy(v).cuda()) for n, v in self.inp.items()}
+        self.x32 = I.widen(self.inp["x"])
+        self.wg32 = I.widen(self.inp["w_gate"])
+        print(f"[full-size] {name}: oracle gate + permutation", flush=True)
+        self.ids, self.tw, self.logits = O.gate_topk(self.x32, self.wg32, self.inp["bias"], w.k)
+        self.counts, self.offsets, self.rop, self.por, _ = O.permute(np.zeros((w.T, 1), np.float32), self.ids, w.E)
+        self.rng = np.random.default_rng(w.seed + 77)
+        self._w32 = {}
+
+    def rerouted(self, ids_gpu):
+        """The same case with the GPU's choice taken for the (validated) near-tie tokens: downstream
+        parity of such a token is defined on the ids the GPU returned; weights from the oracle's logits."""
+        import copy
+        from scipy.special import softmax
+        c = copy.copy(self)
+        differ = (ids_gpu != self.ids).any(axis=1)
+        c.ids = np.where(differ[:, None], ids_gpu, self.ids).astype(np.int32)
+        c.tw = self.tw.copy()
+        sel = np.take_along_axis(self.logits[differ], ids_gpu[differ].astype(np.int64), axis=1)
+        c.tw[differ] = softmax(sel, axis=1).astype(self.tw.dtype)
+        c.counts, c.offsets, c.rop, c.por, _ = O.permute(np.zeros((self.w.T, 1), np.float32), c.ids, self.w.E)
+        return c, int(differ.sum())
+
+    def weight32(self, name, e):
+        key = (name, e)
+        if key not in self._w32:
+            self._w32[key] = I.widen(self.inp[name][e])
+        return self._w32[key]
+
+    def xp_rows(self, rows):
+        """stored tokens of the given permuted rows, widened (Xp rows are bit copies of X rows)"""
+        return self.x32[self.por[rows] // self.w.k]
+
+    def sample_rows(self, n_random):
+        w = self.w
+        rows = set()
+        for e in range(w.E):
+            b, en = int(self.offsets[e]), int(self.offsets[e + 1])
+            if en > b:
+                rows.update([b, en - 1])
+                if en - b < 256:
+                    rows.update(range(b, en, max(1, (en - b) // 8)))
+        rows.update(self.rng.integers(0, w.R, n_random).tolist())
+        return np.array(sorted(rows), dtype=np.int64)
+
+    def oracle_ffn_rows(self, rows, dyp_rows=None):
+        """exact Yp (and dXp) of the given rows: the FFN restricted to those rows, expert by expert"""
+        w = self.w
+        e_of = np.searchsorted(self.offsets, rows, side="right") - 1
+        yp = np.empty((len(rows), w.d), np.float32)
+        dxp = None if dyp_rows is None else np.empty((len(rows), w.d), np.float32)
+        for e in np.unique(e_of):
+            m = np.nonzero(e_of == e)[0]
+            xs = np.ascontiguousarray(self.xp_rows(rows[m]))
+            off = np.array([0, len(m)], np.int32)
+            W1, W3, W2 = (self.weight32(n, e)[None] for n in ("w1", "w3", "w2"))
+            yp[m] = O.ffn_fwd(xs, off, W1, W3, W2)[0]
+            if dyp_rows is not None:
+                dxp[m] = O.ffn_bwd(xs, off, W1, W3, W2, np.ascontiguousarray(dyp_rows[m]))[0]
+        return yp, dxp
+
+
+@pytest.fixture(scope="module", params=WORKLOADS)
+def case(request):
+    c = Case(request.param)
+    yield c
+    del c
+    torch.cuda.empty_cache()
+
+
+def test_gate_and_permutation_in_full(case):
+    w, s, g = case.w, case.s, case.g
+    buf = MoeLayerBuffers(s, want_logits=True)
+    B.moe_gate_topk(s, g["x"], g["w_gate"], g["bias"], buf.topk_ids, buf.topk_w, buf.logits, buf.ws)
+    torch.cuda.synchronize()
+    near = check_gate(host(buf.topk_ids), host(buf.topk_w), host(buf.logits), case.ids, case.tw, case.logits, w.k)
+    print(f"[full-size] {w.name}: {near} near-tie tokens of {w.T}", flush=True)
+    assert near <= max(2, w.T // 200)      # tokens under the near-tie threshold are rare (validated one by one above)
+    ids = torch.from_numpy(case.ids).cuda()
+    B.moe_permute(s, g["x"], ids, buf.counts, buf.offsets, buf.row_of_pair, buf.pair_of_row, buf.x_perm, buf.ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(buf.counts), case.counts)
+    np.testing.assert_array_equal(host(buf.offsets), case.offsets)
+    np.testing.assert_array_equal(host(buf.row_of_pair), case.rop)
+    np.testing.assert_array_equal(host(buf.pair_of_row), case.por)
+    assert int(case.counts.sum()) == w.T * w.k                      # dropless
+    # every permuted row is a bit copy of its token
+    src = torch.from_numpy(case.por // w.k).cuda().long()
+    assert torch.equal(buf.x_perm, g["x"][src])
+
+
+def test_layer_forward_sampled_tokens(case):
+    w, s, g = case.w, case.s, case.g
+    buf = MoeLayerBuffers(s, backward=w.backward)
+    buf.forward(g["x"], g["w_gate"], g["bias"], g["w1"], g["w3"], g["w2"])
+    torch.cuda.synchronize()
+    ids_gpu = host(buf.topk_ids)
+    if not (ids_gpu == case.ids).all():   # near-tie tokens (validated in the gate test): follow the GPU's ids
+        case, n = case.rerouted(ids_gpu)
+        assert n <= max(2, w.T // 200)
+    np.testing.assert_array_equal(host(buf.row_of_pair), case.rop)
+    np.testing.assert_array_equal(host(buf.offsets), case.offsets)
+    n_tok = 48 if w.d * w.f > 2 ** 24 else 128
+    toks = np.unique(case.rng.integers(0, w.T, n_tok))
+    rows = np.concatenate([case.rop[toks * w.k + sl] for sl in range(w.k)])
+    rows = np.unique(np.concatenate([rows, case.sample_rows(0)]))
+    yp_ref, _ = case.oracle_ffn_rows(rows)
+    tol = TOL[tdtype(w)]
+    yp_gpu = host(buf.y_perm[torch.from_numpy(rows).cuda()])
+    assert rel_max(yp_gpu, yp_ref) <= tol
+    pos = {int(r): i for i, r in enumerate(rows)}
+    y_ref = np.zeros((len(toks), w.d))
+    for i, t in enumerate(toks):
+        for sl in range(w.k):
+            y_ref[i] += float(case.tw[t, sl]) * yp_ref[pos[int(case.rop[t * w.k + sl])]].astype(np.float64)
+    assert rel_max(host(buf.y[torch.from_numpy(toks).cuda()]), y_ref) <= tol
+
+
+def test_linear_stages_with_standin_upstream(case):
+    """combine, combine backward, permute backward, gate backward at full size."""
+    w, s, g = case.w, case.s, case.g
+    if not w.backward and w.name != "cfg2_e64k4":
+        pytest.skip("forward-only workload; combine is covered by the cfg2 case")
+    buf = MoeLayerBuffers(s, backward=True)
+    gen = torch.Generator(device="cuda").manual_seed(1234 + w.seed)
+    yp = torch.randn((w.R, w.d), device="cuda", generator=gen).to(tdtype(w))
+    rop = torch.from_numpy(case.rop).cuda()
+    tw = torch.from_numpy(case.tw.astype(np.float32)).cuda()
+    yp64 = host(yp)
+    tol_round = 2.0 ** -8 if w.dtype == "bf16" else 1e-6
+    B.moe_unpermute_combine(s, yp, rop, tw, buf.y)
+    ref = O.unpermute_combine(yp64, case.rop, case.tw.astype(np.float32).astype(np.float64), w.T)
+    assert rel_max(host(buf.y), ref) <= tol_round
+    B.moe_unpermute_combine(s, yp, rop, None, buf.y)
+    assert rel_max(host(buf.y), O.unpermute_combine(yp64, case.rop, None, w.T)) <= tol_round
+    dy = g["dy"] if "dy" in g else torch.randn((w.T, w.d), device="cuda", generator=gen).to(tdtype(w))
+    B.moe_combine_bwd(s, dy, yp, rop, tw, buf.dy_perm, buf.dtopk_w)
+    dYp, dw = O.combine_bwd(host(dy), yp64, case.rop, case.tw.astype(np.float32).astype(np.float64))
+    assert rel_max(host(buf.dy_perm), dYp) <= tol_round
+    assert rel_max(host(buf.dtopk_w), dw) <= 1e-5
+    # gate backward with the oracle's dw (rounded to the fp32 the ABI carries)
+    dw32 = dw.astype(np.float32)
+    dx0 = torch.randn((w.T, w.d), device="cuda", generator=gen).to(tdtype(w))
+    buf.dx.copy_(dx0)
+    ids = torch.from_numpy(case.ids).cuda()
+    B.moe_gate_topk_bwd(s, g["x"], g["w_gate"], ids, tw, torch.from_numpy(dw32).cuda(), buf.dx, buf.dw_gate, buf.ws)
+    dX, dWg, _ = O.gate_bwd(case.x32.astype(np.float64), case.wg32.astype(np.float64), case.ids,
+                            case.tw.astype(np.float32).astype(np.float64), dw32.astype(np.float64), host(dx0))
+    assert rel_max(host(buf.dw_gate), dWg) <= 1e-4
+    assert rel_max(host(buf.dx), dX) <= tol_round
+
+
+def test_grouped_ffn_backward_sampled(case):
+    w, s, g = case.w, case.s, case.g
+    if not w.backward:
+        pytest.skip("forward-only workload")
+    buf = MoeLayerBuffers(s, backward=True)
+    ids = torch.from_numpy(case.ids).cuda()
+    B.moe_permute(s, g["x"], ids, buf.counts, buf.offsets, buf.row_of_pair, buf.pair_of_row, buf.x_perm, buf.ws)
+    gen = torch.Generator(device="cuda").manual_seed(4321 + w.seed)
+    dyp = torch.randn((w.R, w.d), device="cuda", generator=gen).to(tdtype(w))
+    B.moe_grouped_ffn_fwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.y_perm, buf.a_save, buf.b_save,
+                          buf.ws)
+    B.moe_grouped_ffn_bwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.a_save, buf.b_save, dyp,
+                          buf.dx_perm, buf.dw1, buf.dw3, buf.dw2, buf.ws)
+    torch.cuda.synchronize()
+    tol = TOL[tdtype(w)]
+    # (1) whole rows of dXp
+    rows = case.sample_rows(24 if w.d * w.f > 2 ** 24 else 96)
+    dyp_rows = host(dyp[torch.from_numpy(rows).cuda()]).astype(np.float32)
+    _, dxp_ref = case.oracle_ffn_rows(rows, dyp_rows)
+    assert rel_max(host(buf.dx_perm[torch.from_numpy(rows).cuda()]), dxp_ref) <= tol
+    # (2) weight gradients on a subset J of the intermediate channels, over all rows
+    print(f"[full-size] {w.name}: oracle wgrad on a channel subset", flush=True)
+    nJ = 16 if w.d * w.f > 2 ** 24 else 48
+    J = np.unique(np.concatenate([[0, w.f - 1], case.rng.integers(0, w.f, nJ)]))
+    W1 = I.widen(np.ascontiguousarray(case.inp["w1"][:, :, J]))
+    W3 = I.widen(np.ascontiguousarray(case.inp["w3"][:, :, J]))
+    W2 = I.widen(np.ascontiguousarray(case.inp["w2"][:, J, :]))
+    xp32 = case.xp_rows(np.arange(w.R))
+    dyp32 = host(dyp).astype(np.float32)
+    _, dW1, dW3, dW2 = O.ffn_bwd(xp32, case.offsets, W1, W3, W2, dyp32)
+    Jt = torch.from_numpy(J).cuda()
+    assert rel_max(host(buf.dw1[:, :, Jt]), dW1) <= tol
+    assert rel_max(host(buf.dw3[:, :, Jt]), dW3) <= tol
+    assert rel_max(host(buf.dw2[:, Jt, :]), dW2) <= tol
+    for e in np.nonzero(case.counts == 0)[0]:
+        assert float(buf.dw1[e].abs().max()) == 0 and float(buf.dw3[e].abs().max()) == 0 \
+            and float(buf.dw2[e].abs().max()) == 0
+    # (3) the recomputing variant gives the same gradients bit for bit
+    ref = [t.clone() for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2)]
+    B.moe_grouped_ffn_bwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], None, None, dyp,
+                          buf.dx_perm, buf.dw1, buf.dw3, buf.dw2, buf.ws)
+    torch.cuda.synchronize()
+    for a, b in zip(ref, (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2)):
+        assert torch.equal(a, b)
