@@ -161,12 +161,28 @@ __device__ __forceinline__ void topk_softmax_token(float (&v)[kGateMaxNE], int l
     __builtin_amdgcn_wave_barrier();
 }
 
+// Maximum over the 64 lanes, returned wave-uniform: DPP row shifts build the maximum of each
+// row of 16 in its last lane, two row broadcasts carry it to lane 63.
+__device__ __forceinline__ float wave_max_f32(float v) {
+#define MOE_DPP_MAX(ctrl, rmask)                                                                              \
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, v),            \
+                                                                       __builtin_bit_cast(int, v), ctrl, rmask, 0xf, false)))
+    MOE_DPP_MAX(0x111, 0xf);  // row_shr:1
+    MOE_DPP_MAX(0x112, 0xf);  // row_shr:2
+    MOE_DPP_MAX(0x114, 0xf);  // row_shr:4
+    MOE_DPP_MAX(0x118, 0xf);  // row_shr:8
+    MOE_DPP_MAX(0x142, 0xa);  // row_bcast:15 into rows 1 and 3
+    MOE_DPP_MAX(0x143, 0xc);  // row_bcast:31 into rows 2 and 3
+#undef MOE_DPP_MAX
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
 template <int NT>  // expert tiles of 32
 __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wgT,
                                                              const float* __restrict__ bias, int32_t* __restrict__ ids,
                                                              float* __restrict__ wout, float* __restrict__ logits_out,
                                                              int Tn, int d, int E, int k) {
-    extern __shared__ float part[];  // [4][32][NT*32] partial logits, then sel[4][MOE_MAX_EXPERTS]
+    extern __shared__ float part[];  // [4][32][NT*32] partial logits, then the picked logits [4][8][MOE_MAX_EXPERTS]
     constexpr int EP = NT * 32;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, kg = lane >> 5;
@@ -183,20 +199,32 @@ __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __res
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
-    for (int c = 0; c < kq; c += 64) {
-        gbf16x8 a[4];
+    // operands of chunk c+1 are requested before the MFMAs of chunk c (HBM latency, not
+    // bandwidth, is what a 32-token tile has to hide)
+    gbf16x8 a[2][4], b[2][NT][4];
+    auto load_chunk = [&](int c, gbf16x8 (&aa)[4], gbf16x8 (&bb)[NT][4]) {
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) a[s4] = *reinterpret_cast<const gbf16x8*>(xa + c + s4 * 8);
+        for (int s4 = 0; s4 < 4; ++s4) aa[s4] = *reinterpret_cast<const gbf16x8*>(xa + c + s4 * 8);
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            gbf16x8 b[4];
-#pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4)
-                b[s4] = *reinterpret_cast<const gbf16x8*>(wb + (size_t)j * 32 * d + c + s4 * 8);
+        for (int j = 0; j < NT; ++j)
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4)
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s4], b[s4], acc[j], 0, 0, 0);
-        }
+                bb[j][s4] = *reinterpret_cast<const gbf16x8*>(wb + (size_t)j * 32 * d + c + s4 * 8);
+    };
+    auto mma_chunk = [&](const gbf16x8 (&aa)[4], const gbf16x8 (&bb)[NT][4]) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aa[s4], bb[j][s4], acc[j], 0, 0, 0);
+    };
+    load_chunk(0, a[0], b[0]);
+    for (int c = 0; c < kq; c += 128) {   // kq is a multiple of 64
+        const int c1 = c + 64 < kq ? c + 64 : c, c2 = c + 128 < kq ? c + 128 : c;
+        load_chunk(c1, a[1], b[1]);
+        mma_chunk(a[0], b[0]);
+        load_chunk(c2, a[0], b[0]);
+        if (c + 64 < kq) mma_chunk(a[1], b[1]);
     }
     // partial sums -> LDS (accumulator layout: col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4)
     float* mine = part + (size_t)wave * kGateMT * EP;
@@ -226,16 +254,53 @@ __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __res
         }
     }
     __syncthreads();  // partial sums consumed; LDS is reused for the picked logits
-    float* sel = part + wave * MOE_MAX_EXPERTS;
+    // top-k of the wave's 8 tokens, all 8 arg-max reductions of a round in flight together
+    float* sel = part + wave * 8 * MOE_MAX_EXPERTS;  // [8][k]
+    if (logits_out) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = t0 + wave * 8 + i;
+#pragma unroll
+            for (int j = 0; j < kGateMaxNE; ++j)
+                if (t < Tn && lane + 64 * j < E) logits_out[(size_t)t * E + lane + 64 * j] = vals[i][j];
+        }
+    }
+    for (int s = 0; s < k; ++s) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float lv = vals[i][0];
+#pragma unroll
+            for (int j = 1; j < kGateMaxNE; ++j) lv = fmaxf(lv, vals[i][j]);
+            const float m = wave_max_f32(lv);  // uniform
+            // lowest expert index holding the maximum: experts are laid out e = lane + 64*j
+            int be = -1;
+#pragma unroll
+            for (int j = kGateMaxNE - 1; j >= 0; --j) {
+                const uint64_t bal = __ballot(vals[i][j] == m);
+                if (bal) be = 64 * j + __builtin_ctzll(bal);
+            }
+            if ((be & 63) == lane) {
+#pragma unroll
+                for (int j = 0; j < kGateMaxNE; ++j)
+                    if (be == lane + 64 * j) vals[i][j] = -INFINITY;
+            }
+            const int t = t0 + wave * 8 + i;
+            if (lane == 0 && t < Tn) {
+                ids[(size_t)t * k + s] = be;
+                sel[i * MOE_MAX_EXPERTS + s] = m;
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int t = t0 + wave * 8 + i;
         if (t >= Tn) continue;
-        if (logits_out)
-#pragma unroll
-            for (int j = 0; j < kGateMaxNE; ++j)
-                if (lane + 64 * j < E) logits_out[(size_t)t * E + lane + 64 * j] = vals[i][j];
-        topk_softmax_token(vals[i], lane, k, sel, ids + (size_t)t * k, wout + (size_t)t * k);
+        const float* sl = sel + i * MOE_MAX_EXPERTS;
+        const float m0 = sl[0];
+        float z = 0.f;
+        for (int s = 0; s < k; ++s) z += __expf(sl[s] - m0);
+        for (int s = lane; s < k; s += 64) wout[(size_t)t * k + s] = __expf(sl[s] - m0) / z;
     }
 }
 
@@ -302,9 +367,19 @@ __global__ __launch_bounds__(kDwgSlab) void gate_bwd_dwg_partial_kernel(
     if (c < d) {
         for (int t = chunk * kDwgTokens; t < t1; ++t) {
             const float xv = Elem<T>::load(x + (size_t)t * d + c);
-            for (int s = 0; s < k; ++s) {
-                const int e = ids[(size_t)t * k + s];
-                accs[e * kDwgSlab + threadIdx.x] += xv * dl[(size_t)t * k + s];
+            // the k experts of one token are distinct, so their k read-modify-writes are
+            // independent: read up to 8 accumulators, add, write back
+            for (int s0 = 0; s0 < k; s0 += 8) {
+                float v[8];
+                int eo[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    eo[u] = (s0 + u < k ? ids[(size_t)t * k + s0 + u] : 0) * kDwgSlab + threadIdx.x;
+                    v[u] = accs[eo[u]];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < k) accs[eo[u]] = fmaf(xv, dl[(size_t)t * k + s0 + u], v[u]);
             }
         }
         for (int e = 0; e < E; ++e)
@@ -360,8 +435,8 @@ extern "C" moe_status moe_gate_topk(const moe_shape* s, const void* x, const voi
         bf16_t* wgT = static_cast<bf16_t*>(ws);
         gate_transpose_bf16_kernel<<<256, 256, 0, st>>>(static_cast<const bf16_t*>(w_gate), wgT, s->d, s->E, NT * 32);
         const int grid = (s->T + kGateMT - 1) / kGateMT;
-        const size_t lds = (size_t)4 * kGateMT * NT * 32 * sizeof(float) < (size_t)4 * MOE_MAX_EXPERTS * 4
-                               ? (size_t)4 * MOE_MAX_EXPERTS * 4 : (size_t)4 * kGateMT * NT * 32 * sizeof(float);
+        size_t lds = (size_t)4 * kGateMT * NT * 32 * sizeof(float);            // partial logits
+        if (lds < (size_t)4 * 8 * MOE_MAX_EXPERTS * sizeof(float)) lds = (size_t)4 * 8 * MOE_MAX_EXPERTS * sizeof(float);
 #define MOE_GATE_LAUNCH(N)                                                                                         \
     {                                                                                                              \
         static bool attr = false;                                                                                  \

@@ -27,7 +27,7 @@ static inline int num_chunks(int64_t R) { return (int)((R + kChunk - 1) / kChunk
 
 size_t permute_workspace_bytes(const moe_shape* s) {
     const int64_t R = (int64_t)s->T * s->k;
-    return align_up((size_t)num_chunks(R) * s->E * sizeof(int32_t), 256);
+    return 2 * align_up((size_t)num_chunks(R) * s->E * sizeof(int32_t), 256);  // chunk histograms + chunk bases
 }
 
 // ---- 1. per-chunk histogram ---------------------------------------------------
@@ -49,8 +49,11 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __rest
         for (int e = lane; e < E; e += 64) chunk_hist[(size_t)chunk * E + e] = h[e];
 }
 
-// ---- 2. scan: chunk_hist[c][e] becomes the first row of chunk c for expert e -----
-__global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__ chunk_hist, int nchunks, int E,
+// ---- 2. scan: chunk_base[c][e] = first row of chunk c for expert e ---------------------
+// One thread per expert.  Input and output are different arrays, so the loads of the two
+// passes do not wait for the stores and overlap each other.
+__global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __restrict__ chunk_hist,
+                                                           int32_t* __restrict__ chunk_base, int nchunks, int E,
                                                            int32_t* __restrict__ counts,
                                                            int32_t* __restrict__ offsets) {
     __shared__ int32_t cnt[MOE_MAX_EXPERTS];
@@ -58,11 +61,15 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__
     const int e = threadIdx.x;
     if (e < E) {
         int32_t run = 0;
-        for (int c = 0; c < nchunks; ++c) {
-            const int32_t v = chunk_hist[(size_t)c * E + e];
-            chunk_hist[(size_t)c * E + e] = run;
-            run += v;
+        int c = 0;
+        for (; c + 8 <= nchunks; c += 8) {
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) run += v[u];
         }
+        for (; c < nchunks; ++c) run += chunk_hist[(size_t)c * E + e];
         cnt[e] = run;
         counts[e] = run;
     }
@@ -79,8 +86,22 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__
     if (e < E) offsets[e] = off[e];
     if (e == 0) offsets[E] = off[E];
     if (e < E) {
-        const int32_t o = off[e];
-        for (int c = 0; c < nchunks; ++c) chunk_hist[(size_t)c * E + e] += o;
+        int32_t run = off[e];
+        int c = 0;
+        for (; c + 8 <= nchunks; c += 8) {
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                chunk_base[(size_t)(c + u) * E + e] = run;
+                run += v[u];
+            }
+        }
+        for (; c < nchunks; ++c) {
+            chunk_base[(size_t)c * E + e] = run;
+            run += chunk_hist[(size_t)c * E + e];
+        }
     }
 }
 
@@ -265,10 +286,11 @@ extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32
     const int nchunks = num_chunks(R);
     const int nblocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
     int32_t* chunk_hist = static_cast<int32_t*>(ws);
+    int32_t* chunk_base = chunk_hist + align_up((size_t)nchunks * E * sizeof(int32_t), 256) / sizeof(int32_t);
     const size_t lds = (size_t)kWavesPerBlock * E * sizeof(int32_t);
     permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_hist);
-    permute_scan_kernel<<<1, 256, 0, st>>>(chunk_hist, nchunks, E, counts, offsets);
-    permute_rank_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_hist, row_of_pair, pair_of_row);
+    permute_scan_kernel<<<1, 256, 0, st>>>(chunk_hist, chunk_base, nchunks, E, counts, offsets);
+    permute_rank_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_base, row_of_pair, pair_of_row);
     if (x_perm) {
         const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
         const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);
