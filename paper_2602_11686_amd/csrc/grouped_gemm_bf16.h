@@ -311,7 +311,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         // writes those bytes.
         auto zero_tail = [&](int it, char* st) {
             if constexpr (RAGK) {
-                const int k0 = kbeg + it * TK;
+                const int k0 = kbeg + (it >= nk ? it - nk : it) * TK;
                 if (k0 + TK > kend) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)

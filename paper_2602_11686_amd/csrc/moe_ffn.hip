@@ -28,7 +28,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-enum { EPI_STORE = 0, EPI_STORE2 = 1, EPI_SWIGLU = 2, EPI_DH = 3 };
+enum { EPI_STORE = 0, EPI_STORE2 = 1, EPI_SWIGLU = 2, EPI_DH = 3, EPI_STORE_F32 = 4 };
 
 struct Seg {
     const void* A;
@@ -56,7 +56,9 @@ struct GArgs {
 
 template <class T, int EPI>
 __device__ __forceinline__ void epilogue_elem(const GArgs& g, int64_t idx, float a, float b) {
-    if constexpr (EPI == EPI_STORE) {
+    if constexpr (EPI == EPI_STORE_F32) {
+        static_cast<float*>(g.C0)[idx] = a;
+    } else if constexpr (EPI == EPI_STORE) {
         Elem<T>::store(static_cast<T*>(g.C0) + idx, a);
     } else if constexpr (EPI == EPI_STORE2) {
         Elem<T>::store(static_cast<T*>(g.C0) + idx, a);
@@ -382,6 +384,26 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
         else grid = dim3((g.N + 63) / 64, (unsigned)((R + 63) / 64 + g.E), 1);
         gg_f32_kernel<DUAL, EPI, RAGK><<<grid, 256, 0, st>>>(g, fs);
     }
+}
+
+void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, const int32_t* chunk_offsets,
+                          int nchunks, int d, int n_pad, float* partial, hipStream_t st) {
+    GArgs g{};
+    g.offsets = chunk_offsets; g.E = nchunks; g.M = d; g.N = n_pad; g.nseg = 2;
+    g.seg[0] = {x, dl_hi, nullptr};
+    g.seg[1] = {x, dl_lo, nullptr};
+    g.lda = d; g.ldb = n_pad; g.strideC = (int64_t)d * n_pad;
+    g.C0 = partial; g.ldc = n_pad;
+    auto kern = gg256_kernel<1, 0, false, EPI_STORE_F32, true>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kGemmLds);
+        attr_done = true;
+    }
+    int64_t tiles = (int64_t)nchunks * ((d + TM - 1) / TM) * ((n_pad + TN - 1) / TN);
+    tiles = (tiles + 255) / 256 * 256;
+    kern<<<dim3((unsigned)tiles), 512, kGemmLds, st>>>(g);
 }
 
 size_t ffn_fwd_workspace_bytes(const moe_shape* s) {

@@ -401,10 +401,60 @@ __global__ void gate_bwd_dwg_reduce_kernel(const float* __restrict__ partial, fl
 
 static inline int dwg_chunks(int Tn) { return (Tn + kDwgTokens - 1) / kDwgTokens; }
 
+// ---- bf16: dW_g through the grouped GEMM --------------------------------------------------
+// dL is written out densely as two bf16 matrices hi + lo (the pair carries 16 mantissa bits
+// of the fp32 value), tokens are cut into chunks of kMmaChunk, each chunk's X^T * dL is one
+// ragged-K GEMM group, and the chunk partials are added in chunk order.
+constexpr int kMmaChunk = 512;
+static inline int mma_chunks(int Tn) { return (Tn + kMmaChunk - 1) / kMmaChunk; }
+static inline int pad8(int v) { return (v + 7) / 8 * 8; }
+
+// one wavefront per token: dl[t,s] (fp32, for the dx update) and the dense hi/lo rows
+__global__ __launch_bounds__(256) void gate_dl_dense_kernel(const int32_t* __restrict__ ids, const float* __restrict__ w,
+                                                            const float* __restrict__ dw, float* __restrict__ dl,
+                                                            bf16_t* __restrict__ hi, bf16_t* __restrict__ lo, int Tn,
+                                                            int k, int n_pad) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    float dot = 0.f;
+    for (int s = 0; s < k; ++s) dot += w[(size_t)t * k + s] * dw[(size_t)t * k + s];
+    for (int s = lane; s < k; s += 64) dl[(size_t)t * k + s] = w[(size_t)t * k + s] * (dw[(size_t)t * k + s] - dot);
+    for (int e = lane; e < n_pad; e += 64) {
+        float v = 0.f;
+        for (int s = 0; s < k; ++s)
+            if (ids[(size_t)t * k + s] == e) v = w[(size_t)t * k + s] * (dw[(size_t)t * k + s] - dot);
+        const bf16_t h = f32_to_bf16(v);
+        hi[(size_t)t * n_pad + e] = h;
+        lo[(size_t)t * n_pad + e] = f32_to_bf16(v - bf16_to_f32(h));
+    }
+}
+
+__global__ void gate_chunk_offsets_kernel(int32_t* __restrict__ off, int nchunks, int Tn) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= nchunks) off[i] = min(i * kMmaChunk, Tn);
+}
+
+// dw_gate[c][e] = sum over chunks (in chunk order) of partial[chunk][c][e]
+__global__ void gate_bwd_dwg_reduce_mma_kernel(const float* __restrict__ partial, float* __restrict__ dwg, int nchunks,
+                                               int d, int E, int n_pad) {
+    const int64_t n = (int64_t)d * E;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i / E), e = (int)(i - (int64_t)c * E);
+        float a = 0.f;
+        for (int ch = 0; ch < nchunks; ++ch) a += partial[((size_t)ch * d + c) * n_pad + e];
+        dwg[i] = a;
+    }
+}
+
 size_t gate_bwd_workspace_bytes(const moe_shape* s) {
     size_t b = align_up((size_t)s->E * s->d * 4, 256);                 // wgT
     b += align_up((size_t)s->T * s->k * 4, 256);                       // dl
-    b += align_up((size_t)dwg_chunks(s->T) * s->E * s->d * 4, 256);    // partial sums
+    const size_t p_valu = (size_t)dwg_chunks(s->T) * s->E * s->d * 4;
+    const size_t p_mma = (size_t)mma_chunks(s->T) * s->d * pad8(s->E) * 4;
+    b += align_up(p_valu > p_mma ? p_valu : p_mma, 256);               // partial sums
+    b += 2 * align_up((size_t)s->T * pad8(s->E) * 2, 256);             // dense dL, hi and lo
+    b += align_up((size_t)(mma_chunks(s->T) + 1) * 4, 256);            // token chunk offsets
     return b;
 }
 
@@ -471,7 +521,27 @@ static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gat
     float* wgT = static_cast<float*>(cv.take((size_t)s->E * s->d * 4));
     float* dl = static_cast<float*>(cv.take((size_t)s->T * s->k * 4));
     const int nchunks = dwg_chunks(s->T);
-    float* partial = static_cast<float*>(cv.take((size_t)nchunks * s->E * s->d * 4));
+    const size_t p_valu = (size_t)nchunks * s->E * s->d * 4;
+    const size_t p_mma = (size_t)mma_chunks(s->T) * s->d * pad8(s->E) * 4;
+    float* partial = static_cast<float*>(cv.take(p_valu > p_mma ? p_valu : p_mma));
+    const bool mma = sizeof(T) == 2 && s->d % 8 == 0;
+    if (mma) {
+        const int n_pad = pad8(s->E), nch = mma_chunks(s->T);
+        bf16_t* hi = static_cast<bf16_t*>(cv.take((size_t)s->T * n_pad * 2));
+        bf16_t* lo = static_cast<bf16_t*>(cv.take((size_t)s->T * n_pad * 2));
+        int32_t* coff = static_cast<int32_t*>(cv.take((size_t)(nch + 1) * 4));
+        gate_dl_dense_kernel<<<(s->T + 3) / 4, 256, 0, st>>>(ids, w, dw, dl, hi, lo, s->T, s->k, n_pad);
+        gate_chunk_offsets_kernel<<<(nch + 256) / 256, 256, 0, st>>>(coff, nch, s->T);
+        if (dx) {
+            gate_transpose_kernel<T><<<256, 256, 0, st>>>(w_gate, wgT, s->d, s->E);
+            int64_t items = (int64_t)s->T * (s->d / 4);
+            int grid = (int)((items + 255) / 256 > 4096 ? 4096 : (items + 255) / 256);
+            gate_bwd_dx_kernel<T><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, s->T, s->d, s->k);
+        }
+        launch_gate_dwg_gemm(x, hi, lo, coff, nch, s->d, n_pad, partial, st);
+        gate_bwd_dwg_reduce_mma_kernel<<<256, 256, 0, st>>>(partial, dwg, nch, s->d, s->E, n_pad);
+        return launch_status("moe_gate_topk_bwd");
+    }
     gate_dl_kernel<<<(s->T + 255) / 256, 256, 0, st>>>(w, dw, dl, s->T, s->k);
     if (dx) {
         gate_transpose_kernel<T><<<256, 256, 0, st>>>(w_gate, wgT, s->d, s->E);
