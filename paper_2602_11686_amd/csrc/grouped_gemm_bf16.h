@@ -33,9 +33,10 @@ namespace moe {
 
 constexpr int TM = 256, TN = 256, TK = 64;
 constexpr int kStageBytes = 65536;  // 32 KB A + 32 KB B
-constexpr int kGemmLds = 2 * kStageBytes;
+constexpr int kGemmLds = 256 * (512 + 32);  // two 64 KB stages; the epilogue stages a 256-row tile with padded rows
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
 #define LDS_AS __attribute__((address_space(3)))
 
 // Scheduling pattern for one k-step: MFMA, LDS read, MFMA, LDS read, ... then a fence.
@@ -269,21 +270,11 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             }
         }
 
-        // fragments of k-step kk of a stage -> registers
+        // fragments of k-step kk of a stage -> registers.  B first: the MFMAs below walk a[0] x b[0..1],
+        // a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
         auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
             const char* sb = st + 32768;
             const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if constexpr (AT == 0) {
-                    a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + rowform);
-                } else {
-                    const char* p = st + a_rd[i] + kk * 8192;
-                    const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
-                    const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
-                    a[i] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-            }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if constexpr (BT == 1) {
@@ -293,6 +284,17 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                     const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
                     const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
                     b[j] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (AT == 0) {
+                    a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + rowform);
+                } else {
+                    const char* p = st + a_rd[i] + kk * 8192;
+                    const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
+                    const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
+                    a[i] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
                 }
             }
         };
@@ -321,12 +323,14 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             }
         };
 
-        // ---- main loop: two LDS stages.  The DMA of stage it+2 is issued in the middle of
-        // iteration it (as soon as every wavefront has pulled its last fragments of stage it out
-        // of LDS) and has a whole iteration to land; the MFMAs of the last k-step overlap the
-        // first fragment reads of the next stage.  The loop body is branch-free: past the end
-        // it re-loads the last k-tile into the free stage and pulls fragments nobody uses.
-        bf16x8 fa[2][4], fb[2][2];
+        // ---- main loop: two LDS stages, three fragment register sets.
+        // Within iteration `it` the fragments of k-steps 2 and 3 are pulled out of LDS early, so the
+        // barrier that frees stage `it` sits after the MFMAs of k-step 1: the DMA of stage it+2 is
+        // issued there and has about one and a half iterations to land.  The MFMAs of k-steps 2 and 3
+        // run under the DMA issue and the first fragment reads of stage it+1.  The body is
+        // branch-free (past the end it re-loads the last k-tile into the free stage and pulls
+        // fragments nobody uses); the two fragment sets X and Y swap roles every iteration.
+        bf16x8 fa[3][4], fb[3][2];
         const int last = total - 1;
         issue(0, 0);
         issue(last < 1 ? last : 1, 1);
@@ -335,54 +339,173 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         __syncthreads();
         load_frags(smem, 0, fa[0], fb[0]);
 
-        for (int it = 0; it < total; ++it) {
-            const char* st = smem + (it & 1) * kStageBytes;
-            char* nx = smem + ((it + 1) & 1) * kStageBytes;
-            // k-step kk: its 8 MFMAs are interleaved one-to-one with the LDS reads of k-step kk+1
-            load_frags(st, 1, fa[1], fb[1]);
-            mma(fa[0], fb[0]);
-            interleave_mfma_dsread<kReads>();
-            load_frags(st, 2, fa[0], fb[0]);
-            mma(fa[1], fb[1]);
-            interleave_mfma_dsread<kReads>();
-            load_frags(st, 3, fa[1], fb[1]);
-            mma(fa[0], fb[0]);
-            interleave_mfma_dsread<kReads>();
-            // all of this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-            if constexpr (RAGK) {
-                if (it + 1 <= last) zero_tail(it + 1, nx);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            }
-            __syncthreads();
-            issue(it + 2 < last ? it + 2 : last, it & 1);
-            load_frags(nx, 0, fa[0], fb[0]);
-            mma(fa[1], fb[1]);
-            interleave_mfma_dsread<kReads>();
+#define MOE_GEMM_BODY(X, Y)                                                                              \
+        {                                                                                                \
+            const char* st = smem + (it & 1) * kStageBytes;                                              \
+            char* nx = smem + ((it + 1) & 1) * kStageBytes;                                              \
+            load_frags(st, 1, fa[Y], fb[Y]);                                                             \
+            mma(fa[X], fb[X]);                                                                           \
+            interleave_mfma_dsread<kReads>();                                                            \
+            load_frags(st, 2, fa[2], fb[2]);                                                             \
+            load_frags(st, 3, fa[X], fb[X]);                                                             \
+            mma(fa[Y], fb[Y]);                                                                           \
+            interleave_mfma_dsread<2 * kReads>();                                                        \
+            /* this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed */ \
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                  \
+            if constexpr (RAGK) {                                                                        \
+                if (it + 1 <= last) zero_tail(it + 1, nx);                                               \
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                       \
+            }                                                                                            \
+            __syncthreads();                                                                             \
+            issue(it + 2 < last ? it + 2 : last, it & 1);                                                \
+            mma(fa[2], fb[2]);                                                                           \
+            load_frags(nx, 0, fa[Y], fb[Y]);                                                             \
+            mma(fa[X], fb[X]);                                                                           \
+            interleave_mfma_dsread<kReads>();                                                            \
         }
+        int it = 0;
+        for (; it + 1 < total; it += 2) {
+            MOE_GEMM_BODY(0, 1)
+            ++it;
+            MOE_GEMM_BODY(1, 0)
+            --it;
+        }
+        if (it < total) MOE_GEMM_BODY(0, 1)
+#undef MOE_GEMM_BODY
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus load of the last iteration must not outlive the tile
     }
 
-    // ---- epilogue (accumulator layout: col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4) ----
+    // ---- epilogue.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4 inside a 32x32
+    // block) go through LDS so that global memory sees 16-byte accesses along rows: whole 128-byte
+    // lines instead of 2-byte pieces.
+    __syncthreads();  // every wavefront is out of the main loop and every DMA load has landed
     const int64_t cbase = RAGK ? (int64_t)e * g.strideC : 0;
     const int l32e = lane & 31, kge = lane >> 5;
+
+    if constexpr (EPI == EPI_STORE_F32) {  // narrow fp32 output (gate weight gradient): direct stores
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
-            if (row >= m_lim) continue;
-            if constexpr (DUAL) {
-                const int col = n0 + wn * 32 + l32e;
-                if (col < g.N)
-                    epilogue_elem<bf16_t, EPI>(g, cbase + (int64_t)row * g.ldc + col, acc[i][0][r], acc[i][1][r]);
-            } else {
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int col = n0 + wn * 64 + j * 32 + l32e;
-                    if (col < g.N) epilogue_elem<bf16_t, EPI>(g, cbase + (int64_t)row * g.ldc + col, acc[i][j][r], 0.f);
+                    if (row < m_lim && col < g.N)
+                        static_cast<float*>(g.C0)[cbase + (int64_t)row * g.ldc + col] = acc[i][j][r];
                 }
             }
+    } else if constexpr (EPI == EPI_DH) {
+        // dH in fp32 through LDS, 128 columns at a time; then 8 columns per thread: read A, B,
+        // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).
+        constexpr int RS = 128 * 4 + 32;  // staging row stride in bytes
+        for (int p = 0; p < 2; ++p) {
+            if ((wn >> 1) == p) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
+                            const int col = (wn & 1) * 64 + j * 32 + l32e;
+                            *reinterpret_cast<float*>(smem + row * RS + col * 4) = acc[i][j][r];
+                        }
+            }
+            __syncthreads();
+            for (int item = threadIdx.x; item < 256 * 16; item += 512) {
+                const int row = item >> 4, cg = item & 15;
+                const int grow = m0 + row, gcol = n0 + p * 128 + cg * 8;
+                if (grow < m_lim && gcol < g.N) {
+                    const int64_t idx = (int64_t)grow * g.ldc + gcol;
+                    const f32x4v d0 = *reinterpret_cast<const f32x4v*>(smem + row * RS + cg * 32);
+                    const f32x4v d1 = *reinterpret_cast<const f32x4v*>(smem + row * RS + cg * 32 + 16);
+                    const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+                    const u32x4 av = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + idx);
+                    const u32x4 bv = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + idx);
+                    u32x4 oh, oa, ob;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float hh[2], da[2], db[2];
+#pragma unroll
+                        for (int z = 0; z < 2; ++z) {
+                            const float A = __uint_as_float(z ? (av[q] & 0xFFFF0000u) : (av[q] << 16));
+                            const float B = __uint_as_float(z ? (bv[q] & 0xFFFF0000u) : (bv[q] << 16));
+                            const float sA = silu_f(A);
+                            hh[z] = sA * B;
+                            da[z] = dh[2 * q + z] * B * silu_grad_f(A);
+                            db[z] = dh[2 * q + z] * sA;
+                        }
+                        oh[q] = (uint32_t)f32_to_bf16(hh[0]) | ((uint32_t)f32_to_bf16(hh[1]) << 16);
+                        oa[q] = (uint32_t)f32_to_bf16(da[0]) | ((uint32_t)f32_to_bf16(da[1]) << 16);
+                        ob[q] = (uint32_t)f32_to_bf16(db[0]) | ((uint32_t)f32_to_bf16(db[1]) << 16);
+                    }
+                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = oh;
+                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = oa;
+                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = ob;
+                }
+            }
+            __syncthreads();
+        }
+    } else {
+        // bf16 tiles: stage [256 rows][ROWB bytes (+16)], then 16 bytes per lane along rows.
+        constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
+        constexpr int RS = ROWB + 16;
+        auto put = [&](int row, int col, float v) {
+            *reinterpret_cast<bf16_t*>(smem + row * RS + col * 2) = f32_to_bf16(v);
+        };
+        // rows x (ROWB/16) pieces; piece -> (destination matrix, column)
+        auto flush = [&](bf16_t* dst0, bf16_t* dst1, int cols0) {
+            __syncthreads();
+            constexpr int PPR = ROWB / 16;  // pieces per row
+            for (int item = threadIdx.x; item < 256 * PPR; item += 512) {
+                const int row = item / PPR, pc = item - row * PPR;
+                const int grow = m0 + row;
+                int col = pc * 8;
+                bf16_t* dst = dst0;
+                if (dst1 && col >= cols0) { col -= cols0; dst = dst1; }
+                const int gcol = n0 + col;
+                if (grow < m_lim && gcol < g.N)
+                    *reinterpret_cast<u32x4*>(dst + cbase + (int64_t)grow * g.ldc + gcol) =
+                        *reinterpret_cast<const u32x4*>(smem + row * RS + pc * 16);
+            }
+            __syncthreads();
+        };
+        if constexpr (EPI == EPI_SWIGLU) {
+            for (int pass = 0; pass < (g.S0 ? 3 : 1); ++pass) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
+                        const float a = acc[i][0][r], b = acc[i][1][r];
+                        put(row, wn * 32 + l32e, pass == 0 ? silu_f(a) * b : pass == 1 ? a : b);
+                    }
+                bf16_t* dst = pass == 0 ? static_cast<bf16_t*>(g.C0)
+                                        : const_cast<bf16_t*>(static_cast<const bf16_t*>(pass == 1 ? g.S0 : g.S1));
+                flush(dst, nullptr, 0);
+            }
+        } else if constexpr (DUAL) {  // EPI_STORE2: first 128 columns -> C0, second 128 -> C1
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
+                    put(row, wn * 32 + l32e, acc[i][0][r]);
+                    put(row, 128 + wn * 32 + l32e, acc[i][1][r]);
+                }
+            flush(static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
+        } else {  // EPI_STORE
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
+                        put(row, wn * 64 + j * 32 + l32e, acc[i][j][r]);
+                    }
+            flush(static_cast<bf16_t*>(g.C0), nullptr, 0);
         }
     }
 }
