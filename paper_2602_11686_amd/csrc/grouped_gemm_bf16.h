@@ -1,6 +1,6 @@
-// Grouped bf16 GEMM for CDNA4 (gfx950): 256x256x64 workgroup tiles, 8 wavefronts,
+// Grouped bf16 GEMM for CDNA4 (gfx950): 256x256x32 workgroup tiles, 8 wavefronts,
 // MFMA 32x32x16 bf16 with fp32 accumulators, operands streamed HBM -> LDS by the
-// DMA path of the global loads (no register staging), double-buffered.
+// DMA path of the global loads (no register staging) into a ring of four LDS stages.
 //
 // One template covers the six products of the expert FFN (paper section 3.1;
 // 6*H*H' FLOPs per routed token forward, backward twice that):
@@ -15,9 +15,9 @@
 //       C_e [M][N] = sum over the rows of expert e;  an expert without rows gets zeros.
 //
 // An operand tile whose contraction index is contiguous in memory ("row form") is
-// kept in LDS as 256 rows x 128 B and read with ds_read_b128; the 16-byte piece p of
-// row r sits in slot p ^ ((r >> 1) & 7).  An operand tile whose other index is contiguous
-// ("k-row form") is kept as 64 k-rows x 512 B and read with the transposing LDS read
+// kept in LDS as 256 rows x 64 B and read with ds_read_b128; the 16-byte piece p of
+// row r sits in slot p ^ ((r >> 2) & 3).  An operand tile whose other index is contiguous
+// ("k-row form") is kept as 32 k-rows x 512 B and read with the transposing LDS read
 // (ds_read_b64_tr_b16: lane i of a 16-lane group receives column i of a 4(k) x 16 block);
 // piece p of k-row q sits in slot p ^ (2*(q&3) + 8*(q&1)).  Both swizzles make every LDS
 // read instruction of the main loop conflict-free on the 64 banks.  A DMA load writes
@@ -31,9 +31,11 @@
 
 namespace moe {
 
-constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int kStageBytes = 65536;  // 32 KB A + 32 KB B
-constexpr int kGemmLds = 256 * (512 + 32);  // two 64 KB stages; the epilogue stages a 256-row tile with padded rows
+constexpr int TM = 256, TN = 256, TK = 32;
+constexpr int kStages = 4;
+constexpr int kStageBytes = 32768;  // 16 KB A + 16 KB B
+constexpr int kBOff = 16384;        // B tile inside a stage
+constexpr int kGemmLds = 256 * (512 + 32);  // four 32 KB stages; the epilogue stages a 256-row tile with padded rows
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4v __attribute__((ext_vector_type(4)));
@@ -51,7 +53,7 @@ __device__ __forceinline__ void interleave_mfma_dsread() {
 }
 
 // slot = piece ^ swz: chosen so that the rows one LDS read instruction touches fall into different banks
-__device__ __forceinline__ int swz_rows(int row) { return (row >> 1) & 7; }              // 128-byte rows, b128 reads
+__device__ __forceinline__ int swz_rows(int row) { return (row >> 2) & 3; }              // 64-byte rows, b128 reads
 __device__ __forceinline__ int swz_krow(int q) { return 2 * (q & 3) + 8 * (q & 1); }      // 512-byte k-rows, tr reads
 
 // 16 bytes per lane, global -> LDS, without passing through registers: lane l lands at
@@ -171,19 +173,19 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             B2seg[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;
         }
         const int64_t lda = g.lda, ldb = g.ldb;
-        // row form: chunk c = wave*4 + i covers rows 8c .. 8c+7; lane -> row 8c + lane/8, slot lane%8
+        // row form: chunk c = wave*2 + i covers rows 16c .. 16c+15; lane -> row 16c + lane/4, slot lane%4
         // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
-        int64_t a_off[4], b_off[4];  // element offsets of this lane's 16-byte pieces (k-independent part)
-        int a_q[4], b_q[4];          // k-row form: the k-row inside the stage
-        bool b_second[4] = {false, false, false, false};  // DUAL: piece comes from the second matrix
+        int64_t a_off[2], b_off[2];  // element offsets of this lane's 16-byte pieces (k-independent part)
+        int a_q[2], b_q[2];          // k-row form: the k-row inside the stage
+        bool b_second[2] = {false, false};  // DUAL: piece comes from the second matrix
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = wave * 4 + i;
+        for (int i = 0; i < 2; ++i) {
+            const int c = wave * 2 + i;
             if constexpr (AT == 0) {
-                const int r = c * 8 + (lane >> 3);
+                const int r = c * 16 + (lane >> 2);
                 int gr = m0 + r;
                 gr = gr < m_lim ? gr : m_lim - 1;  // rows past the expert's end: any valid row (masked at the store)
-                a_off[i] = (int64_t)gr * lda + ((lane & 7) ^ swz_rows(r)) * 8;
+                a_off[i] = (int64_t)gr * lda + ((lane & 3) ^ swz_rows(r)) * 8;
                 a_q[i] = 0;
             } else {
                 a_q[i] = c * 2 + (lane >> 5);
@@ -192,10 +194,10 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                 a_off[i] = col;
             }
             if constexpr (BT == 1) {
-                const int r = c * 8 + (lane >> 3);
+                const int r = c * 16 + (lane >> 2);
                 int gn = n0 + r;
                 gn = gn < g.N ? gn : g.N - 1;
-                b_off[i] = (int64_t)gn * ldb + ((lane & 7) ^ swz_rows(r)) * 8;
+                b_off[i] = (int64_t)gn * ldb + ((lane & 3) ^ swz_rows(r)) * 8;
                 b_q[i] = 0;
             } else {
                 b_q[i] = c * 2 + (lane >> 5);
@@ -209,7 +211,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             }
         }
         const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
-        const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 4096);
+        const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 2048);
 
         auto issue = [&](int it, int buf) {
             const int sg = it >= nk ? 1 : 0;
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             const bf16_t* A = sg ? Aseg[1] : Aseg[0];
             const bf16_t* B = sg ? Bseg[1] : Bseg[0];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 2; ++i) {
                 if constexpr (AT == 0) {
                     dma16(A + a_off[i] + k0, st + i * 1024);
                 } else {
@@ -228,15 +230,15 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                 }
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 2; ++i) {
                 if constexpr (BT == 1) {
-                    dma16(B + b_off[i] + k0, st + 32768 + i * 1024);
+                    dma16(B + b_off[i] + k0, st + kBOff + i * 1024);
                 } else {
                     int kr = k0 + b_q[i];
                     if constexpr (RAGK) kr = kr < kend ? kr : kend - 1;
                     const bf16_t* src = B;
                     if constexpr (DUAL) src = b_second[i] ? (sg ? B2seg[1] : B2seg[0]) : B;
-                    dma16(src + (int64_t)kr * ldb + b_off[i], st + 32768 + i * 1024);
+                    dma16(src + (int64_t)kr * ldb + b_off[i], st + kBOff + i * 1024);
                 }
             }
         };
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if constexpr (AT == 0) {
-                a_rd[i] = (wm * 128 + i * 32 + l32) * 128;
+                a_rd[i] = (wm * 128 + i * 32 + l32) * 64;
             } else {
                 const int col = wm * 128 + i * 32 + tr_lane_col;
                 a_rd[i] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         for (int j = 0; j < 2; ++j) {
             const int cb = DUAL ? (j * 128 + wn * 32) : (wn * 64 + j * 32);
             if constexpr (BT == 1) {
-                b_rd[j] = (cb + l32) * 128;
+                b_rd[j] = (cb + l32) * 64;
             } else {
                 const int col = cb + tr_lane_col;
                 b_rd[j] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         // fragments of k-step kk of a stage -> registers.  B first: the MFMAs below walk a[0] x b[0..1],
         // a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
         auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
-            const char* sb = st + 32768;
+            const char* sb = st + kBOff;
             const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -316,63 +318,49 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                 const int k0 = kbeg + (it >= nk ? it - nk : it) * TK;
                 if (k0 + TK > kend) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < 2; ++i)
                         if (k0 + a_q[i] >= kend)
-                            *reinterpret_cast<u32x4*>(st + (wave * 4 + i) * 1024 + lane * 16) = (u32x4){0, 0, 0, 0};
+                            *reinterpret_cast<u32x4*>(st + (wave * 2 + i) * 1024 + lane * 16) = (u32x4){0, 0, 0, 0};
                 }
             }
         };
 
-        // ---- main loop: two LDS stages, three fragment register sets.
-        // Within iteration `it` the fragments of k-steps 2 and 3 are pulled out of LDS early, so the
-        // barrier that frees stage `it` sits after the MFMAs of k-step 1: the DMA of stage it+2 is
-        // issued there and has about one and a half iterations to land.  The MFMAs of k-steps 2 and 3
-        // run under the DMA issue and the first fragment reads of stage it+1.  The body is
-        // branch-free (past the end it re-loads the last k-tile into the free stage and pulls
-        // fragments nobody uses); the two fragment sets X and Y swap roles every iteration.
-        bf16x8 fa[3][4], fb[3][2];
+        // ---- main loop: a ring of four 32 KB stages (32-wide k-tiles), two k-steps per stage.
+        // The barrier in the middle of iteration `it` publishes stage it+1 and frees the buffer of
+        // stage it, into which the DMA of stage it+4 is issued at once: three stages are in flight
+        // and each has three iterations to land.  (With two 64-wide stages the loop ran at the pace
+        // of the DMA round trip: a load issued at one barrier had to be complete at the next.)
+        // The body is branch-free: past the end it re-loads the last k-tile into the free buffer and
+        // pulls fragments nobody uses.
+        bf16x8 fa[2][4], fb[2][2];
         const int last = total - 1;
-        issue(0, 0);
-        issue(last < 1 ? last : 1, 1);
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+#pragma unroll
+        for (int q = 0; q < kStages; ++q) issue(q < last ? q : last, q);
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // stage 0 has landed
         zero_tail(0, smem);
         __syncthreads();
         load_frags(smem, 0, fa[0], fb[0]);
 
-#define MOE_GEMM_BODY(X, Y)                                                                              \
-        {                                                                                                \
-            const char* st = smem + (it & 1) * kStageBytes;                                              \
-            char* nx = smem + ((it + 1) & 1) * kStageBytes;                                              \
-            load_frags(st, 1, fa[Y], fb[Y]);                                                             \
-            mma(fa[X], fb[X]);                                                                           \
-            interleave_mfma_dsread<kReads>();                                                            \
-            load_frags(st, 2, fa[2], fb[2]);                                                             \
-            load_frags(st, 3, fa[X], fb[X]);                                                             \
-            mma(fa[Y], fb[Y]);                                                                           \
-            interleave_mfma_dsread<2 * kReads>();                                                        \
-            /* this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed */ \
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                  \
-            if constexpr (RAGK) {                                                                        \
-                if (it + 1 <= last) zero_tail(it + 1, nx);                                               \
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                       \
-            }                                                                                            \
-            __syncthreads();                                                                             \
-            issue(it + 2 < last ? it + 2 : last, it & 1);                                                \
-            mma(fa[2], fb[2]);                                                                           \
-            load_frags(nx, 0, fa[Y], fb[Y]);                                                             \
-            mma(fa[X], fb[X]);                                                                           \
-            interleave_mfma_dsread<kReads>();                                                            \
+        for (int it = 0; it < total; ++it) {
+            const char* st = smem + (it & (kStages - 1)) * kStageBytes;
+            char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
+            load_frags(st, 1, fa[1], fb[1]);
+            mma(fa[0], fb[0]);
+            interleave_mfma_dsread<kReads>();
+            // this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
+            // (the eight youngest loads belong to stages it+2 and it+3)
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            if constexpr (RAGK) {
+                if (it + 1 <= last) zero_tail(it + 1, nx);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            __syncthreads();
+            issue(it + kStages < last ? it + kStages : last, it & (kStages - 1));
+            load_frags(nx, 0, fa[0], fb[0]);
+            mma(fa[1], fb[1]);
+            interleave_mfma_dsread<kReads>();
         }
-        int it = 0;
-        for (; it + 1 < total; it += 2) {
-            MOE_GEMM_BODY(0, 1)
-            ++it;
-            MOE_GEMM_BODY(1, 0)
-            --it;
-        }
-        if (it < total) MOE_GEMM_BODY(0, 1)
-#undef MOE_GEMM_BODY
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus load of the last iteration must not outlive the tile
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last iterations must not outlive the tile
     }
 
     // ---- epilogue.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4 inside a 32x32
