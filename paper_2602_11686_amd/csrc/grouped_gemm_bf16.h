@@ -35,7 +35,7 @@ constexpr int TM = 256, TN = 256, TK = 32;
 constexpr int kStages = 4;
 constexpr int kStageBytes = 32768;  // 16 KB A + 16 KB B
 constexpr int kBOff = 16384;        // B tile inside a stage
-constexpr int kGemmLds = 256 * (512 + 32);  // four 32 KB stages; the epilogue stages a 256-row tile with padded rows
+constexpr int kGemmLds = kStages * kStageBytes + 2 * (MOE_MAX_EXPERTS + 1) * 4 + 8;  // ring + expert table
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4v __attribute__((ext_vector_type(4)));
@@ -86,423 +86,515 @@ __device__ __forceinline__ void walk_tile(int local, int nm, int n_tiles, int& m
     nt = nbase + (local - m * width);
 }
 
-// Logical tile id -> (expert, first row, row limit, n-tile) when M is ragged: expert-major.
-__device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets, int E, int n_tiles, int L,
-                                            int& e_out, int& m0, int& m_lim, int& nt) {
-    int acc = 0;
-    for (int e = 0; e < E; ++e) {
-        const int b = offsets[e], en = offsets[e + 1];
-        const int nm = (en - b + TM - 1) / TM;
-        const int cnt = nm * n_tiles;
-        if (L < acc + cnt) {
-            int m;
-            walk_tile(L - acc, nm, n_tiles, m, nt);
-            m0 = b + m * TM;
-            m_lim = en;
-            e_out = e;
-            return true;
-        }
-        acc += cnt;
-    }
-    return false;
-}
-
 // Workgroups are dealt round-robin to the 8 XCDs.  Hand out the logical tile order in
 // blocks of 32 (one block = what the 32 CUs of one XCD run together); consecutive blocks go
 // to different XCDs, so the XCDs work on neighbouring blocks and share panels in the
-// memory-side cache.  gridDim.x is a multiple of 256.
+// memory-side cache.  The grid is a multiple of 256 workgroups.
 __device__ __forceinline__ int logical_tile(int wg) {
     const int xcd = wg & 7, idx = wg >> 3;
     return (((idx >> 5) * 8 + xcd) << 5) + (idx & 31);
 }
 
+struct TileDesc {
+    int e, m0, m_lim, n0, kbeg, kend, nk;  // nk = k-stages per K segment
+    bool valid;
+};
+
+// The kernel is persistent: one workgroup per CU walks the tiles  logical_tile(blockIdx.x + r *
+// gridDim.x), r = 0, 1, ...  Inside a tile the DMA loads run four k-stages ahead of the MFMAs; the
+// first stages of the next tile are requested before the current tile's epilogue, so they arrive
+// while the epilogue runs (no workgroup relaunch, no cold prologue per tile).
 template <int AT, int BT, bool DUAL, int EPI, bool RAGK>
 __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
     static_assert(RAGK ? (AT == 1 && BT == 0) : (AT == 0), "operand forms");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    int32_t* t_off = reinterpret_cast<int32_t*>(smem + kStages * kStageBytes);  // [E+1] rows of each expert
+    int32_t* t_pref = t_off + MOE_MAX_EXPERTS + 1;                              // [E+1] tiles before expert e
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 2, wn = wave & 3;  // 2 x 4 wavefronts, 128 x 64 each
-
-    const int L = logical_tile(blockIdx.x);
-    const int n_out = DUAL ? TN / 2 : TN;  // output columns per tile
+    const int n_out = DUAL ? TN / 2 : TN;     // output columns per tile
     const int n_tiles = (g.N + n_out - 1) / n_out;
-    int e, m0, m_lim, nt, kbeg, kend;
-    if constexpr (RAGK) {
-        const int m_tiles = (g.M + TM - 1) / TM;
-        const int per = m_tiles * n_tiles;
-        const int oi = L / per;
-        if (oi >= g.E) return;
-        e = g.order ? g.order[oi] : oi;  // heaviest experts first
-        int m;
-        walk_tile(L - oi * per, m_tiles, n_tiles, m, nt);
-        m0 = m * TM;
-        m_lim = g.M;
-        kbeg = g.offsets[e];
-        kend = g.offsets[e + 1];
-    } else {
-        if (!decode_tile(g.offsets, g.E, n_tiles, L, e, m0, m_lim, nt)) return;
-        kbeg = 0;
-        kend = g.K;
+    const int m_tiles_k = (g.M + TM - 1) / TM;  // ragged K only
+
+    // ---- expert table in LDS: rows of each expert and the number of tiles before it ----
+    for (int i = threadIdx.x; i <= g.E; i += 512) t_off[i] = g.offsets[i];
+    __syncthreads();
+    if (wave == 0) {  // exclusive scan of the per-expert tile counts: 4 experts per lane, then across lanes
+        int c[4], sum = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = lane * 4 + u;
+            c[u] = 0;
+            if (e < g.E) c[u] = RAGK ? m_tiles_k * n_tiles : ((t_off[e + 1] - t_off[e] + TM - 1) / TM) * n_tiles;
+            sum += c[u];
+        }
+        int incl = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += o;
+        }
+        int run = incl - sum;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = lane * 4 + u;
+            if (e <= g.E) t_pref[e] = run;
+            run += c[u];
+        }
     }
-    const int n0 = nt * n_out;
+    __syncthreads();
+    const int total_tiles = t_pref[g.E];
 
-    f32x16 acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    auto decode = [&](int round) -> TileDesc {
+        TileDesc t;
+        const int L = logical_tile(blockIdx.x + round * gridDim.x);
+        t.valid = L < total_tiles;
+        t.e = 0; t.m0 = 0; t.m_lim = 0; t.n0 = 0; t.kbeg = 0; t.kend = 0; t.nk = 0;
+        if (!t.valid) return t;
+        int m, nt;
+        if constexpr (RAGK) {
+            const int per = m_tiles_k * n_tiles;
+            const int oi = L / per;
+            t.e = g.order ? g.order[oi] : oi;  // heaviest experts first
+            walk_tile(L - oi * per, m_tiles_k, n_tiles, m, nt);
+            t.m0 = m * TM;
+            t.m_lim = g.M;
+            t.kbeg = t_off[t.e];
+            t.kend = t_off[t.e + 1];
+        } else {
+            // the expert whose tile range holds L: every lane tests a few experts, a ballot picks it
+            int found = 0;
+            for (int j = 0; j < MOE_MAX_EXPERTS / 64; ++j) {
+                const int e = lane + 64 * j;
+                const bool hit = e < g.E && t_pref[e] <= L && L < t_pref[e + 1];
+                const uint64_t bal = __ballot(hit);
+                if (bal) found = 64 * j + __builtin_ctzll(bal);
+            }
+            t.e = __builtin_amdgcn_readfirstlane(found);
+            const int b = t_off[t.e], en = t_off[t.e + 1];
+            walk_tile(L - t_pref[t.e], (en - b + TM - 1) / TM, n_tiles, m, nt);
+            t.m0 = b + m * TM;
+            t.m_lim = en;
+            t.kend = g.K;
+        }
+        t.n0 = nt * n_out;
+        t.nk = (t.kend - t.kbeg + TK - 1) / TK;  // exact when M is ragged (K % 32 == 0)
+        t.e = __builtin_amdgcn_readfirstlane(t.e);
+        t.m0 = __builtin_amdgcn_readfirstlane(t.m0);
+        t.m_lim = __builtin_amdgcn_readfirstlane(t.m_lim);
+        t.n0 = __builtin_amdgcn_readfirstlane(t.n0);
+        t.kbeg = __builtin_amdgcn_readfirstlane(t.kbeg);
+        t.kend = __builtin_amdgcn_readfirstlane(t.kend);
+        t.nk = __builtin_amdgcn_readfirstlane(t.nk);
+        return t;
+    };
 
-    const int nk = (kend - kbeg + TK - 1) / TK;  // exact when M is ragged (K % 64 == 0)
-    const int total = nk * g.nseg;
+    // ================= issue side: DMA loads of stream position p into ring buffer p & 3 =================
+    const int64_t lda = g.lda, ldb = g.ldb;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 2048);
+    // row form: chunk c = wave*2 + i covers rows 16c .. 16c+15; lane -> row 16c + lane/4, slot lane%4
+    // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
+    TileDesc di;                  // tile whose stages are being issued
+    di.valid = false; di.e = 0; di.m0 = 0; di.m_lim = 0; di.n0 = 0; di.kbeg = 0; di.kend = 0; di.nk = 0;
+    uint32_t a_off[2], b_off[2];  // element offsets of this lane's 16-byte pieces (k-independent part)
+    bool b_second[2] = {false, false};
+    const bf16_t* iA[2];
+    const bf16_t* iB[2];
+    const bf16_t* iB2[2];
+    const int q_row[2] = {(wave * 2 + 0) * 2 + (lane >> 5), (wave * 2 + 1) * 2 + (lane >> 5)};
 
-    if (total > 0) {
-        // ---- per-lane source addressing of the DMA loads (fixed for the whole tile walk) ----
-        // Everything the main loop needs sits in registers: a scalar load inside the loop would
-        // share the LDS reads' wait counter and serialise them.
-        const bf16_t* Aseg[2];
-        const bf16_t* Bseg[2];
-        const bf16_t* B2seg[2];
+    auto setup_issue = [&]() {
 #pragma unroll
         for (int sgi = 0; sgi < 2; ++sgi) {
             const int q = sgi < g.nseg ? sgi : 0;
-            const int64_t eoff = RAGK ? 0 : (int64_t)e * g.strideB;
-            Aseg[sgi] = static_cast<const bf16_t*>(g.seg[q].A);
-            Bseg[sgi] = static_cast<const bf16_t*>(g.seg[q].B) + eoff;
-            B2seg[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;
+            const int64_t eoff = RAGK ? 0 : (int64_t)di.e * g.strideB;
+            iA[sgi] = static_cast<const bf16_t*>(g.seg[q].A);
+            iB[sgi] = static_cast<const bf16_t*>(g.seg[q].B) + eoff;
+            iB2[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;
         }
-        const int64_t lda = g.lda, ldb = g.ldb;
-        // row form: chunk c = wave*2 + i covers rows 16c .. 16c+15; lane -> row 16c + lane/4, slot lane%4
-        // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
-        int64_t a_off[2], b_off[2];  // element offsets of this lane's 16-byte pieces (k-independent part)
-        int a_q[2], b_q[2];          // k-row form: the k-row inside the stage
-        bool b_second[2] = {false, false};  // DUAL: piece comes from the second matrix
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = wave * 2 + i;
             if constexpr (AT == 0) {
                 const int r = c * 16 + (lane >> 2);
-                int gr = m0 + r;
-                gr = gr < m_lim ? gr : m_lim - 1;  // rows past the expert's end: any valid row (masked at the store)
-                a_off[i] = (int64_t)gr * lda + ((lane & 3) ^ swz_rows(r)) * 8;
-                a_q[i] = 0;
+                int gr = di.m0 + r;
+                gr = gr < di.m_lim ? gr : di.m_lim - 1;  // rows past the expert's end: any valid row (masked at the store)
+                a_off[i] = (uint32_t)gr * (uint32_t)lda + ((lane & 3) ^ swz_rows(r)) * 8;
             } else {
-                a_q[i] = c * 2 + (lane >> 5);
-                int col = m0 + ((lane & 31) ^ swz_krow(a_q[i])) * 8;
+                int col = di.m0 + ((lane & 31) ^ swz_krow(q_row[i])) * 8;
                 col = col < g.M ? col : g.M - 8;
                 a_off[i] = col;
             }
             if constexpr (BT == 1) {
                 const int r = c * 16 + (lane >> 2);
-                int gn = n0 + r;
+                int gn = di.n0 + r;
                 gn = gn < g.N ? gn : g.N - 1;
-                b_off[i] = (int64_t)gn * ldb + ((lane & 3) ^ swz_rows(r)) * 8;
-                b_q[i] = 0;
+                b_off[i] = (uint32_t)gn * (uint32_t)ldb + ((lane & 3) ^ swz_rows(r)) * 8;
             } else {
-                b_q[i] = c * 2 + (lane >> 5);
-                const int piece = (lane & 31) ^ swz_krow(b_q[i]);
+                const int piece = (lane & 31) ^ swz_krow(q_row[i]);
                 int col;
-                if constexpr (DUAL) col = n0 + (piece & 15) * 8;  // pieces 16..31 come from the second matrix
-                else col = n0 + piece * 8;
+                if constexpr (DUAL) col = di.n0 + (piece & 15) * 8;  // pieces 16..31 come from the second matrix
+                else col = di.n0 + piece * 8;
                 col = col < g.N ? col : g.N - 8;
                 b_off[i] = col;
                 if constexpr (DUAL) b_second[i] = (piece >> 4) != 0;
             }
         }
-        const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
-        const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 2048);
-
-        auto issue = [&](int it, int buf) {
-            const int sg = it >= nk ? 1 : 0;
-            const int k0 = kbeg + (it - sg * nk) * TK;
-            const uint32_t st = lds_wave + buf * kStageBytes;
-            const bf16_t* A = sg ? Aseg[1] : Aseg[0];
-            const bf16_t* B = sg ? Bseg[1] : Bseg[0];
+    };
+    // k-stage `stage` of tile di -> ring buffer `buf` (always exactly four DMA instructions per wavefront)
+    auto issue = [&](int stage, int buf) {
+        const int sg = stage >= di.nk ? 1 : 0;
+        const int k0 = di.kbeg + (stage - sg * di.nk) * TK;
+        const uint32_t st = lds_wave + buf * kStageBytes;
+        const bf16_t* A = sg ? iA[1] : iA[0];
+        const bf16_t* B = sg ? iB[1] : iB[0];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                if constexpr (AT == 0) {
-                    dma16(A + a_off[i] + k0, st + i * 1024);
-                } else {
-                    int kr = k0 + a_q[i];
-                    kr = kr < kend ? kr : kend - 1;  // past the expert's rows: a valid row; zeroed in LDS below
-                    dma16(A + (int64_t)kr * lda + a_off[i], st + i * 1024);
-                }
+        for (int i = 0; i < 2; ++i) {
+            if constexpr (AT == 0) {
+                dma16(A + a_off[i] + k0, st + i * 1024);
+            } else {
+                // k-rows past the expert's rows read a row of zeros: they add nothing to the sums
+                const int kr = k0 + q_row[i];
+                const bf16_t* src = kr < di.kend ? A + (int64_t)kr * lda + a_off[i]
+                                                 : static_cast<const bf16_t*>(g.zero_row) + (lane & 31) * 8;
+                dma16(src, st + i * 1024);
             }
+        }
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                if constexpr (BT == 1) {
-                    dma16(B + b_off[i] + k0, st + kBOff + i * 1024);
-                } else {
-                    int kr = k0 + b_q[i];
-                    if constexpr (RAGK) kr = kr < kend ? kr : kend - 1;
-                    const bf16_t* src = B;
-                    if constexpr (DUAL) src = b_second[i] ? (sg ? B2seg[1] : B2seg[0]) : B;
-                    dma16(src + (int64_t)kr * ldb + b_off[i], st + kBOff + i * 1024);
-                }
+        for (int i = 0; i < 2; ++i) {
+            if constexpr (BT == 1) {
+                dma16(B + b_off[i] + k0, st + kBOff + i * 1024);
+            } else {
+                int kr = k0 + q_row[i];
+                if constexpr (RAGK) kr = kr < di.kend ? kr : di.kend - 1;  // any valid (finite) row: it meets zeros
+                const bf16_t* src = B;
+                if constexpr (DUAL) src = b_second[i] ? (sg ? iB2[1] : iB2[0]) : B;
+                dma16(src + (int64_t)kr * ldb + b_off[i], st + kBOff + i * 1024);
             }
-        };
+        }
+    };
 
-        // ---- per-lane LDS read addressing ----
-        const int l32 = lane & 31, kg = lane >> 5;
-        const int a_sw = swz_rows(l32);  // the same for all tiles of 32 rows
-        // k-row form (transposing reads): lane -> group g16 = lane/16, i16 = lane%16
-        const int g16 = lane >> 4, i16 = lane & 15;
-        const int tr_krow = (g16 >> 1) * 8 + (i16 >> 2);  // + kk*16 + t*4
-        const int tr_sw = swz_krow(tr_krow);              // kk*16 + t*4 do not change the swizzle
-        const int tr_lane_col = (g16 & 1) * 16 + (i16 & 3) * 4;
-        int a_rd[4], b_rd[2];  // byte offsets inside the operand tile, without the k-step term
+    // ================= compute side =================
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int a_sw = swz_rows(l32);  // the same for all tiles of 32 rows
+    // k-row form (transposing reads): lane -> group g16 = lane/16, i16 = lane%16
+    const int g16 = lane >> 4, i16 = lane & 15;
+    const int tr_krow = (g16 >> 1) * 8 + (i16 >> 2);  // + kk*16 + t*4
+    const int tr_sw = swz_krow(tr_krow);              // kk*16 + t*4 do not change the swizzle
+    const int tr_lane_col = (g16 & 1) * 16 + (i16 & 3) * 4;
+    int a_rd[4], b_rd[2];  // byte offsets inside the operand tile, without the k-step term
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if constexpr (AT == 0) {
+            a_rd[i] = (wm * 128 + i * 32 + l32) * 64;
+        } else {
+            const int col = wm * 128 + i * 32 + tr_lane_col;
+            a_rd[i] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int cb = DUAL ? (j * 128 + wn * 32) : (wn * 64 + j * 32);
+        if constexpr (BT == 1) {
+            b_rd[j] = (cb + l32) * 64;
+        } else {
+            const int col = cb + tr_lane_col;
+            b_rd[j] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
+        }
+    }
+    // fragments of k-step kk of a stage -> registers.  B first: the MFMAs below walk a[0] x b[0..1],
+    // a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
+    auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+        const char* sb = st + kBOff;
+        const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if constexpr (BT == 1) {
+                b[j] = *reinterpret_cast<const bf16x8*>(sb + b_rd[j] + rowform);
+            } else {
+                const char* p = sb + b_rd[j] + kk * 8192;
+                const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
+                const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
+                b[j] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if constexpr (AT == 0) {
-                a_rd[i] = (wm * 128 + i * 32 + l32) * 64;
+                a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + rowform);
             } else {
-                const int col = wm * 128 + i * 32 + tr_lane_col;
-                a_rd[i] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
+                const char* p = st + a_rd[i] + kk * 8192;
+                const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
+                const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
+                a[i] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
+    };
+    f32x16 acc[4][2];
+    auto zero_acc = [&]() {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int cb = DUAL ? (j * 128 + wn * 32) : (wn * 64 + j * 32);
-            if constexpr (BT == 1) {
-                b_rd[j] = (cb + l32) * 64;
-            } else {
-                const int col = cb + tr_lane_col;
-                b_rd[j] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
-            }
-        }
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    };
+    auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? 2 : 4);
 
-        // fragments of k-step kk of a stage -> registers.  B first: the MFMAs below walk a[0] x b[0..1],
-        // a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
-        auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
-            const char* sb = st + kBOff;
-            const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                if constexpr (BT == 1) {
-                    b[j] = *reinterpret_cast<const bf16x8*>(sb + b_rd[j] + rowform);
-                } else {
-                    const char* p = sb + b_rd[j] + kk * 8192;
-                    const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
-                    const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
-                    b[j] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+    // ---- epilogue of one tile.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
+    // inside a 32x32 block) go through LDS, 64 rows at a time (block i of both wavefront rows), so that
+    // global memory sees 16-byte accesses along rows.  `stg` is the 32 KB ring buffer of the stage
+    // consumed last; the other three buffers hold the next tile's first stages.
+    auto epilogue_zero = [&](const TileDesc& t) {  // ragged K, expert without rows: exact zeros, no staging needed
+        const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
+        {
+            constexpr int PPR = 32;
+            for (int item = threadIdx.x; item < 256 * PPR; item += 512) {
+                const int row = t.m0 + item / PPR;
+                int col = (item % PPR) * 8;
+                bf16_t* dst = static_cast<bf16_t*>(g.C0);
+                if (DUAL && col >= 128) { col -= 128; dst = static_cast<bf16_t*>(g.C1); }
+                if (row < t.m_lim && t.n0 + col < g.N) {
+                    if constexpr (EPI == EPI_STORE_F32) {
+                        float* d = static_cast<float*>(g.C0) + cbase + (int64_t)row * g.ldc + t.n0 + col;
+                        for (int z = 0; z < 8; ++z) d[z] = 0.f;
+                    } else {
+                        *reinterpret_cast<u32x4*>(dst + cbase + (int64_t)row * g.ldc + t.n0 + col) = (u32x4){0, 0, 0, 0};
+                    }
                 }
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if constexpr (AT == 0) {
-                    a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + rowform);
-                } else {
-                    const char* p = st + a_rd[i] + kk * 8192;
-                    const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
-                    const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
-                    a[i] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-            }
-        };
-        auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
+        }
+    };
+    auto epilogue = [&](const TileDesc& t, char* stg) {
+        const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
+        if constexpr (EPI == EPI_STORE_F32) {  // narrow fp32 output (gate weight gradient): direct stores
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-        };
-        constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? 2 : 4);
-
-        // Ragged K: the k-rows of the last stage that lie past the expert's rows are zeroed in the
-        // A tile (the B tile holds a valid, finite row there).  Each lane overwrites exactly the
-        // 16 bytes its own DMA loads delivered, after it has waited for them: no other wavefront
-        // writes those bytes.
-        auto zero_tail = [&](int it, char* st) {
-            if constexpr (RAGK) {
-                const int k0 = kbeg + (it >= nk ? it - nk : it) * TK;
-                if (k0 + TK > kend) {
+                for (int r = 0; r < 16; ++r) {
+                    const int row = t.m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
-                        if (k0 + a_q[i] >= kend)
-                            *reinterpret_cast<u32x4*>(st + (wave * 2 + i) * 1024 + lane * 16) = (u32x4){0, 0, 0, 0};
+                    for (int j = 0; j < 2; ++j) {
+                        const int col = t.n0 + wn * 64 + j * 32 + l32;
+                        if (row < t.m_lim && col < g.N)
+                            static_cast<float*>(g.C0)[cbase + (int64_t)row * g.ldc + col] = acc[i][j][r];
+                    }
+                }
+        } else if constexpr (EPI == EPI_DH) {
+            // dH in fp32 through LDS, 64 rows x 128 columns at a time; then 8 columns per thread: read A, B,
+            // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).  Staging rows are 512 B; the
+            // 16-byte piece index is XORed with 8*((row>>2)&1) so that the two lane halves hit different banks.
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                for (int p = 0; p < 2; ++p) {
+                    if ((wn >> 1) == p) {
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+                                const int col = (wn & 1) * 64 + j * 32 + l32;
+                                const int piece = (col >> 2) ^ (((sr >> 2) & 1) << 3);
+                                *reinterpret_cast<float*>(stg + sr * 512 + piece * 16 + (col & 3) * 4) = acc[i][j][r];
+                            }
+                    }
+                    __syncthreads();
+                    for (int item = threadIdx.x; item < 64 * 16; item += 512) {
+                        const int sr = item >> 4, cg = item & 15;
+                        const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
+                        if (grow < t.m_lim && gcol < g.N) {
+                            const int64_t idx = (int64_t)grow * g.ldc + gcol;
+                            const int sw = ((sr >> 2) & 1) << 3;
+                            const f32x4v d0 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg) ^ sw) * 16);
+                            const f32x4v d1 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg + 1) ^ sw) * 16);
+                            const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+                            const u32x4 av = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + idx);
+                            const u32x4 bv = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + idx);
+                            u32x4 oh, oa, ob;
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                float hh[2], da[2], db[2];
+#pragma unroll
+                                for (int z = 0; z < 2; ++z) {
+                                    const float A = __uint_as_float(z ? (av[q] & 0xFFFF0000u) : (av[q] << 16));
+                                    const float B = __uint_as_float(z ? (bv[q] & 0xFFFF0000u) : (bv[q] << 16));
+                                    const float sA = silu_f(A);
+                                    hh[z] = sA * B;
+                                    da[z] = dh[2 * q + z] * B * silu_grad_f(A);
+                                    db[z] = dh[2 * q + z] * sA;
+                                }
+                                oh[q] = (uint32_t)f32_to_bf16(hh[0]) | ((uint32_t)f32_to_bf16(hh[1]) << 16);
+                                oa[q] = (uint32_t)f32_to_bf16(da[0]) | ((uint32_t)f32_to_bf16(da[1]) << 16);
+                                ob[q] = (uint32_t)f32_to_bf16(db[0]) | ((uint32_t)f32_to_bf16(db[1]) << 16);
+                            }
+                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = oh;
+                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = oa;
+                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = ob;
+                        }
+                    }
+                    __syncthreads();
                 }
             }
-        };
-
-        // ---- main loop: a ring of four 32 KB stages (32-wide k-tiles), two k-steps per stage.
-        // The barrier in the middle of iteration `it` publishes stage it+1 and frees the buffer of
-        // stage it, into which the DMA of stage it+4 is issued at once: three stages are in flight
-        // and each has three iterations to land.  (With two 64-wide stages the loop ran at the pace
-        // of the DMA round trip: a load issued at one barrier had to be complete at the next.)
-        // The body is branch-free: past the end it re-loads the last k-tile into the free buffer and
-        // pulls fragments nobody uses.
-        bf16x8 fa[2][4], fb[2][2];
-        const int last = total - 1;
+        } else {
+            // bf16 tiles: stage [64 rows][ROWB bytes], piece index XORed with 8*((row>>2)&1), then 16 bytes
+            // per lane along rows.
+            constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
+            constexpr int PPR = ROWB / 16;  // pieces per row
+            auto put = [&](int sr, int col, float v) {
+                const int piece = (col >> 3) ^ (((sr >> 2) & 1) << 3);
+                *reinterpret_cast<bf16_t*>(stg + sr * ROWB + piece * 16 + (col & 7) * 2) = f32_to_bf16(v);
+            };
+            auto flush = [&](int i, bf16_t* dst0, bf16_t* dst1, int cols0) {
+                __syncthreads();
+                for (int item = threadIdx.x; item < 64 * PPR; item += 512) {
+                    const int sr = item / PPR, pc = item - sr * PPR;
+                    const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
+                    int col = pc * 8;
+                    bf16_t* dst = dst0;
+                    if (dst1 && col >= cols0) { col -= cols0; dst = dst1; }
+                    const int gcol = t.n0 + col;
+                    if (grow < t.m_lim && gcol < g.N)
+                        *reinterpret_cast<u32x4*>(dst + cbase + (int64_t)grow * g.ldc + gcol) =
+                            *reinterpret_cast<const u32x4*>(stg + sr * ROWB + ((pc ^ (((sr >> 2) & 1) << 3)) << 4));
+                }
+                __syncthreads();
+            };
 #pragma unroll
-        for (int q = 0; q < kStages; ++q) issue(q < last ? q : last, q);
-        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // stage 0 has landed
-        zero_tail(0, smem);
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (EPI == EPI_SWIGLU) {
+                    for (int pass = 0; pass < (g.S0 ? 3 : 1); ++pass) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+                            const float a = acc[i][0][r], b = acc[i][1][r];
+                            put(sr, wn * 32 + l32, pass == 0 ? silu_f(a) * b : pass == 1 ? a : b);
+                        }
+                        bf16_t* dst = pass == 0 ? static_cast<bf16_t*>(g.C0)
+                                                : const_cast<bf16_t*>(static_cast<const bf16_t*>(pass == 1 ? g.S0 : g.S1));
+                        flush(i, dst, nullptr, 0);
+                    }
+                } else if constexpr (DUAL) {  // EPI_STORE2: first 128 columns -> C0, second 128 -> C1
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+                        put(sr, wn * 32 + l32, acc[i][0][r]);
+                        put(sr, 128 + wn * 32 + l32, acc[i][1][r]);
+                    }
+                    flush(i, static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
+                } else {  // EPI_STORE
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+                            put(sr, wn * 64 + j * 32 + l32, acc[i][j][r]);
+                        }
+                    flush(i, static_cast<bf16_t*>(g.C0), nullptr, 0);
+                }
+            }
+        }
+    };
+
+    // ================= the tiles of this workgroup =================
+    // Per tile: stages 0..3 are in flight when its loop starts (stages 0..2 were issued before the
+    // previous tile's epilogue, stage 3 after it); the barrier in the middle of iteration `it`
+    // publishes stage it+1 and frees the buffer of stage it, into which stage it+4 is issued at once.
+    bf16x8 fa[2][4], fb[2][2];
+    auto wait_loads = [&](int stages_allowed) {  // at most that many of the youngest stage loads may be pending
+        if (stages_allowed >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (stages_allowed == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    int round = 0;
+    TileDesc t = decode(round);
+    while (t.valid && t.nk == 0) {  // ragged K: leading experts without rows
+        epilogue_zero(t);
+        t = decode(++round);
+    }
+    if (!t.valid) return;
+    di = t;
+    setup_issue();
+    {
+        const int tot0 = t.nk * g.nseg;
+        for (int q = 0; q < kStages && q < tot0; ++q) issue(q, q);
+    }
+    for (;;) {
+        const int total = t.nk * g.nseg;
+        zero_acc();
+        // stage 0 must have landed: it is followed by min(total, 4) - 1 younger stage loads
+        if (total >= 4) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        else wait_loads(total - 1);
         __syncthreads();
         load_frags(smem, 0, fa[0], fb[0]);
-
-        for (int it = 0; it < total; ++it) {
+        int it = 0;
+        // ---- hot loop: branch-free ----
+        for (; it + kStages < total; ++it) {
             const char* st = smem + (it & (kStages - 1)) * kStageBytes;
-            char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
+            const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
             load_frags(st, 1, fa[1], fb[1]);
             mma(fa[0], fb[0]);
             interleave_mfma_dsread<kReads>();
             // this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
             // (the eight youngest loads belong to stages it+2 and it+3)
             asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
-            if constexpr (RAGK) {
-                if (it + 1 <= last) zero_tail(it + 1, nx);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            }
             __syncthreads();
-            issue(it + kStages < last ? it + kStages : last, it & (kStages - 1));
+            issue(it + kStages, it & (kStages - 1));
             load_frags(nx, 0, fa[0], fb[0]);
             mma(fa[1], fb[1]);
             interleave_mfma_dsread<kReads>();
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last iterations must not outlive the tile
-    }
-
-    // ---- epilogue.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4 inside a 32x32
-    // block) go through LDS so that global memory sees 16-byte accesses along rows: whole 128-byte
-    // lines instead of 2-byte pieces.
-    __syncthreads();  // every wavefront is out of the main loop and every DMA load has landed
-    const int64_t cbase = RAGK ? (int64_t)e * g.strideC : 0;
-    const int l32e = lane & 31, kge = lane >> 5;
-
-    if constexpr (EPI == EPI_STORE_F32) {  // narrow fp32 output (gate weight gradient): direct stores
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int col = n0 + wn * 64 + j * 32 + l32e;
-                    if (row < m_lim && col < g.N)
-                        static_cast<float*>(g.C0)[cbase + (int64_t)row * g.ldc + col] = acc[i][j][r];
-                }
-            }
-    } else if constexpr (EPI == EPI_DH) {
-        // dH in fp32 through LDS, 128 columns at a time; then 8 columns per thread: read A, B,
-        // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).
-        constexpr int RS = 128 * 4 + 32;  // staging row stride in bytes
-        for (int p = 0; p < 2; ++p) {
-            if ((wn >> 1) == p) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
-                            const int col = (wn & 1) * 64 + j * 32 + l32e;
-                            *reinterpret_cast<float*>(smem + row * RS + col * 4) = acc[i][j][r];
-                        }
-            }
+        // ---- the last (up to four) stages: nothing left to issue for this tile ----
+        for (; it < total; ++it) {
+            const char* st = smem + (it & (kStages - 1)) * kStageBytes;
+            const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
+            load_frags(st, 1, fa[1], fb[1]);
+            mma(fa[0], fb[0]);
+            interleave_mfma_dsread<kReads>();
+            const int rem = total - 1 - it;  // stages after this one, all issued already
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            wait_loads(rem - 1);
             __syncthreads();
-            for (int item = threadIdx.x; item < 256 * 16; item += 512) {
-                const int row = item >> 4, cg = item & 15;
-                const int grow = m0 + row, gcol = n0 + p * 128 + cg * 8;
-                if (grow < m_lim && gcol < g.N) {
-                    const int64_t idx = (int64_t)grow * g.ldc + gcol;
-                    const f32x4v d0 = *reinterpret_cast<const f32x4v*>(smem + row * RS + cg * 32);
-                    const f32x4v d1 = *reinterpret_cast<const f32x4v*>(smem + row * RS + cg * 32 + 16);
-                    const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
-                    const u32x4 av = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + idx);
-                    const u32x4 bv = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + idx);
-                    u32x4 oh, oa, ob;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float hh[2], da[2], db[2];
-#pragma unroll
-                        for (int z = 0; z < 2; ++z) {
-                            const float A = __uint_as_float(z ? (av[q] & 0xFFFF0000u) : (av[q] << 16));
-                            const float B = __uint_as_float(z ? (bv[q] & 0xFFFF0000u) : (bv[q] << 16));
-                            const float sA = silu_f(A);
-                            hh[z] = sA * B;
-                            da[z] = dh[2 * q + z] * B * silu_grad_f(A);
-                            db[z] = dh[2 * q + z] * sA;
-                        }
-                        oh[q] = (uint32_t)f32_to_bf16(hh[0]) | ((uint32_t)f32_to_bf16(hh[1]) << 16);
-                        oa[q] = (uint32_t)f32_to_bf16(da[0]) | ((uint32_t)f32_to_bf16(da[1]) << 16);
-                        ob[q] = (uint32_t)f32_to_bf16(db[0]) | ((uint32_t)f32_to_bf16(db[1]) << 16);
-                    }
-                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = oh;
-                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = oa;
-                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = ob;
-                }
-            }
-            __syncthreads();
+            if (rem > 0) load_frags(nx, 0, fa[0], fb[0]);
+            mma(fa[1], fb[1]);
+            interleave_mfma_dsread<kReads>();
         }
-    } else {
-        // bf16 tiles: stage [256 rows][ROWB bytes (+16)], then 16 bytes per lane along rows.
-        constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
-        constexpr int RS = ROWB + 16;
-        auto put = [&](int row, int col, float v) {
-            *reinterpret_cast<bf16_t*>(smem + row * RS + col * 2) = f32_to_bf16(v);
-        };
-        // rows x (ROWB/16) pieces; piece -> (destination matrix, column)
-        auto flush = [&](bf16_t* dst0, bf16_t* dst1, int cols0) {
-            __syncthreads();
-            constexpr int PPR = ROWB / 16;  // pieces per row
-            for (int item = threadIdx.x; item < 256 * PPR; item += 512) {
-                const int row = item / PPR, pc = item - row * PPR;
-                const int grow = m0 + row;
-                int col = pc * 8;
-                bf16_t* dst = dst0;
-                if (dst1 && col >= cols0) { col -= cols0; dst = dst1; }
-                const int gcol = n0 + col;
-                if (grow < m_lim && gcol < g.N)
-                    *reinterpret_cast<u32x4*>(dst + cbase + (int64_t)grow * g.ldc + gcol) =
-                        *reinterpret_cast<const u32x4*>(smem + row * RS + pc * 16);
-            }
-            __syncthreads();
-        };
-        if constexpr (EPI == EPI_SWIGLU) {
-            for (int pass = 0; pass < (g.S0 ? 3 : 1); ++pass) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
-                        const float a = acc[i][0][r], b = acc[i][1][r];
-                        put(row, wn * 32 + l32e, pass == 0 ? silu_f(a) * b : pass == 1 ? a : b);
-                    }
-                bf16_t* dst = pass == 0 ? static_cast<bf16_t*>(g.C0)
-                                        : const_cast<bf16_t*>(static_cast<const bf16_t*>(pass == 1 ? g.S0 : g.S1));
-                flush(dst, nullptr, 0);
-            }
-        } else if constexpr (DUAL) {  // EPI_STORE2: first 128 columns -> C0, second 128 -> C1
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
-                    put(row, wn * 32 + l32e, acc[i][0][r]);
-                    put(row, 128 + wn * 32 + l32e, acc[i][1][r]);
-                }
-            flush(static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
-        } else {  // EPI_STORE
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = wm * 128 + i * 32 + (r >> 2) * 8 + kge * 4 + (r & 3);
-                        put(row, wn * 64 + j * 32 + l32e, acc[i][j][r]);
-                    }
-            flush(static_cast<bf16_t*>(g.C0), nullptr, 0);
+        // ---- next tile: its first stages are requested before this tile's epilogue ----
+        // (every DMA load of this tile has landed and every wavefront is past the last barrier, after
+        // which nobody reads LDS any more: all four buffers are free)
+        TileDesc nt = decode(++round);
+        while (nt.valid && nt.nk == 0) {
+            epilogue_zero(nt);
+            nt = decode(++round);
         }
+        int ntot = 0;
+        if (nt.valid) {
+            di = nt;
+            setup_issue();
+            ntot = nt.nk * g.nseg;
+            for (int q = 0; q < kStages - 1 && q < ntot; ++q) issue(q, q);
+        }
+        epilogue(t, smem + (kStages - 1) * kStageBytes);
+        if (!nt.valid) break;
+        if (ntot >= kStages) issue(kStages - 1, kStages - 1);
+        t = nt;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 // Experts sorted by row count, heaviest first (one workgroup; E <= 256): the wgrad tiles of a
 // heavy expert take longest, so they are started first.
 __global__ __launch_bounds__(256) void expert_order_kernel(const int32_t* __restrict__ offsets, int E,
-                                                           int32_t* __restrict__ order) {
+                                                           int32_t* __restrict__ order, uint32_t* __restrict__ zero_row) {
     const int e = threadIdx.x;
+    if (e < 128) zero_row[e] = 0u;  // the 512-byte row of zeros the wgrad loads read past an expert's last row
     if (e >= E) return;
     const int mine = offsets[e + 1] - offsets[e];
     int rank = 0;

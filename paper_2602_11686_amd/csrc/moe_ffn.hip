@@ -52,6 +52,7 @@ struct GArgs {
     const void* S1;        // saved B
     int64_t ldc;
     const int32_t* order;  // ragged K: experts by row count, heaviest first (may be null)
+    const void* zero_row;  // ragged K: 512 bytes of zeros in device memory
 };
 
 template <class T, int EPI>
@@ -349,7 +350,9 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
     if (s->dtype == MOE_BF16) {
         constexpr bool fast_form = RAGK ? (AT == 1 && BT == 0) : (AT == 0);
         if constexpr (fast_form) {
+            // (the kernel keeps per-lane element offsets in 32 bits)
             const bool ok = g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8 &&
+                            (uint64_t)R * (uint64_t)g.lda < (1ull << 32) && (uint64_t)g.N * (uint64_t)g.ldb < (1ull << 32) &&
                             (RAGK ? (g.M >= 8) : (g.K % TK == 0));
             if (ok) {
                 auto kern = gg256_kernel<AT, BT, DUAL, EPI, RAGK>;
@@ -359,13 +362,8 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
                                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
                     attr_done = true;
                 }
-                const int n_out = DUAL ? TN / 2 : TN;
-                const int64_t n_tiles = (g.N + n_out - 1) / n_out;
-                int64_t tiles;
-                if (RAGK) tiles = (int64_t)g.E * ((g.M + TM - 1) / TM) * n_tiles;
-                else tiles = ((R + TM - 1) / TM + g.E) * n_tiles;
-                tiles = (tiles + 255) / 256 * 256;
-                kern<<<dim3((unsigned)tiles), 512, kGemmLds, st>>>(g);
+                (void)R;
+                kern<<<dim3(256), 512, kGemmLds, st>>>(g);  // persistent: one workgroup per CU
                 return;
             }
         }
@@ -387,8 +385,9 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
 }
 
 void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, const int32_t* chunk_offsets,
-                          int nchunks, int d, int n_pad, float* partial, hipStream_t st) {
+                          int nchunks, int d, int n_pad, float* partial, const void* zero_row, hipStream_t st) {
     GArgs g{};
+    g.zero_row = zero_row;
     g.offsets = chunk_offsets; g.E = nchunks; g.M = d; g.N = n_pad; g.nseg = 2;
     g.seg[0] = {x, dl_hi, nullptr};
     g.seg[1] = {x, dl_lo, nullptr};
@@ -401,16 +400,14 @@ void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, c
                                   kGemmLds);
         attr_done = true;
     }
-    int64_t tiles = (int64_t)nchunks * ((d + TM - 1) / TM) * ((n_pad + TN - 1) / TN);
-    tiles = (tiles + 255) / 256 * 256;
-    kern<<<dim3((unsigned)tiles), 512, kGemmLds, st>>>(g);
+    kern<<<dim3(256), 512, kGemmLds, st>>>(g);
 }
 
 size_t ffn_fwd_workspace_bytes(const moe_shape* s) {
     return align_up((size_t)s->T * s->k * s->f * el_size(s), 256);  // H
 }
 size_t ffn_bwd_workspace_bytes(const moe_shape* s) {
-    return 5 * align_up((size_t)s->T * s->k * s->f * el_size(s), 256) + 1024;  // H, dA, dB, (A, B when recomputing), expert order
+    return 5 * align_up((size_t)s->T * s->k * s->f * el_size(s), 256) + 2048;  // H, dA, dB, (A, B when recomputing), expert order, a row of zeros
 }
 
 }  // namespace moe
@@ -493,7 +490,8 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     void* dA = cv.take(rf);
     void* dB = cv.take(rf);
     int32_t* order = static_cast<int32_t*>(cv.take(1024));
-    expert_order_kernel<<<1, 256, 0, st>>>(offsets, s->E, order);
+    void* zero_row = cv.take(512);
+    expert_order_kernel<<<1, 256, 0, st>>>(offsets, s->E, order, static_cast<uint32_t*>(zero_row));
     if (!a_save || !b_save) {  // expert-only recomputation: rebuild A and B (H is rewritten below anyway)
         void* A = cv.take(rf);
         void* B = cv.take(rf);
@@ -523,7 +521,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
         g.offsets = offsets; g.E = s->E; g.M = s->f; g.N = s->d; g.nseg = 1;
         g.seg[0] = {H, dy_perm, nullptr};
         g.lda = s->f; g.ldb = s->d; g.strideC = (int64_t)s->f * s->d;
-        g.C0 = dw2; g.ldc = s->d; g.order = order;
+        g.C0 = dw2; g.ldc = s->d; g.order = order; g.zero_row = zero_row;
         launch_gg<1, 0, false, EPI_STORE, true>(s, g, R, st);
     }
     {  // [dW1|dW3][e] = Xp_e^T * [dA_e|dB_e]
@@ -531,7 +529,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
         g.offsets = offsets; g.E = s->E; g.M = s->d; g.N = s->f; g.nseg = 1;
         g.seg[0] = {x_perm, dA, dB};
         g.lda = s->d; g.ldb = s->f; g.strideC = (int64_t)s->d * s->f;
-        g.C0 = dw1; g.C1 = dw3; g.ldc = s->f; g.order = order;
+        g.C0 = dw1; g.C1 = dw3; g.ldc = s->f; g.order = order; g.zero_row = zero_row;
         launch_gg<1, 0, true, EPI_STORE2, true>(s, g, R, st);
     }
     return launch_status(who);

@@ -430,8 +430,9 @@ __global__ __launch_bounds__(256) void gate_dl_dense_kernel(const int32_t* __res
     }
 }
 
-__global__ void gate_chunk_offsets_kernel(int32_t* __restrict__ off, int nchunks, int Tn) {
+__global__ void gate_chunk_offsets_kernel(int32_t* __restrict__ off, int nchunks, int Tn, uint32_t* __restrict__ zero_row) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 128) zero_row[i] = 0u;
     if (i <= nchunks) off[i] = min(i * kMmaChunk, Tn);
 }
 
@@ -454,7 +455,7 @@ size_t gate_bwd_workspace_bytes(const moe_shape* s) {
     const size_t p_mma = (size_t)mma_chunks(s->T) * s->d * pad8(s->E) * 4;
     b += align_up(p_valu > p_mma ? p_valu : p_mma, 256);               // partial sums
     b += 2 * align_up((size_t)s->T * pad8(s->E) * 2, 256);             // dense dL, hi and lo
-    b += align_up((size_t)(mma_chunks(s->T) + 1) * 4, 256);            // token chunk offsets
+    b += align_up((size_t)(mma_chunks(s->T) + 1) * 4, 256) + 512;      // token chunk offsets, a row of zeros
     return b;
 }
 
@@ -531,14 +532,15 @@ static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gat
         bf16_t* lo = static_cast<bf16_t*>(cv.take((size_t)s->T * n_pad * 2));
         int32_t* coff = static_cast<int32_t*>(cv.take((size_t)(nch + 1) * 4));
         gate_dl_dense_kernel<<<(s->T + 3) / 4, 256, 0, st>>>(ids, w, dw, dl, hi, lo, s->T, s->k, n_pad);
-        gate_chunk_offsets_kernel<<<(nch + 256) / 256, 256, 0, st>>>(coff, nch, s->T);
+        uint32_t* zero_row = static_cast<uint32_t*>(cv.take(512));
+        gate_chunk_offsets_kernel<<<(nch + 256) / 256, 256, 0, st>>>(coff, nch, s->T, zero_row);
         if (dx) {
             gate_transpose_kernel<T><<<256, 256, 0, st>>>(w_gate, wgT, s->d, s->E);
             int64_t items = (int64_t)s->T * (s->d / 4);
             int grid = (int)((items + 255) / 256 > 4096 ? 4096 : (items + 255) / 256);
             gate_bwd_dx_kernel<T><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, s->T, s->d, s->k);
         }
-        launch_gate_dwg_gemm(x, hi, lo, coff, nch, s->d, n_pad, partial, st);
+        launch_gate_dwg_gemm(x, hi, lo, coff, nch, s->d, n_pad, partial, zero_row, st);
         gate_bwd_dwg_reduce_mma_kernel<<<256, 256, 0, st>>>(partial, dwg, nch, s->d, s->E, n_pad);
         return launch_status("moe_gate_topk_bwd");
     }

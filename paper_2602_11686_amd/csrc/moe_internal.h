@@ -40,9 +40,9 @@ size_t gate_bwd_workspace_bytes(const moe_shape* s);
 // dW_g partials on the matrix cores (implemented next to the grouped GEMM):
 //   partial[c][m][n] = sum over the tokens t of chunk c of x[t][m] * (dl_hi[t][n] + dl_lo[t][n])
 // x [T][d] bf16, dl_hi / dl_lo [T][n_pad] bf16, chunk_offsets [nchunks+1] token ranges,
-// partial [nchunks][d][n_pad] fp32.
+// partial [nchunks][d][n_pad] fp32; zero_row: 512 bytes of zeros in device memory.
 void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, const int32_t* chunk_offsets,
-                          int nchunks, int d, int n_pad, float* partial, hipStream_t st);
+                          int nchunks, int d, int n_pad, float* partial, const void* zero_row, hipStream_t st);
 
 // ---- device-side element helpers -------------------------------------------
 typedef uint16_t bf16_t;  // raw bits
