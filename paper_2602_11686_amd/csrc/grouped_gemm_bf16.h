@@ -35,10 +35,34 @@ constexpr int TM = 256, TN = 256, TK = 32;
 constexpr int kStages = 4;
 constexpr int kStageBytes = 32768;  // 16 KB A + 16 KB B
 constexpr int kBOff = 16384;        // B tile inside a stage
+#ifndef MOE_GEMM_WAVES
+#define MOE_GEMM_WAVES 8
+#endif
+// 8 wavefronts (wave tile 128x64, two per SIMD) is the measured optimum: with 4 (wave tile 128x128, a third
+// less LDS read traffic) a single wavefront per SIMD no longer hides its own LDS latency (-20 %).
+constexpr int kWaves = MOE_GEMM_WAVES;
+constexpr int kThreads = kWaves * 64;
+constexpr int kWN = kWaves / 2;            // wavefronts along N (two along M)
+constexpr int NJ = 8 / kWN;                // 32-column MFMA blocks per wavefront
+constexpr int CPW = 16 / kWaves;           // 1 KB DMA chunks per wavefront per operand tile
+#define MOE_STR2(x) #x
+#define MOE_STR(x) MOE_STR2(x)
+#define MOE_VMCNT(n) "s_waitcnt vmcnt(" MOE_STR(n) ")"
+#if MOE_GEMM_WAVES == 4
+#define MOE_VM1 8
+#define MOE_VM2 16
+#define MOE_VM3 24
+#else
+#define MOE_VM1 4
+#define MOE_VM2 8
+#define MOE_VM3 12
+#endif
 constexpr int kGemmLds = kStages * kStageBytes + 2 * (MOE_MAX_EXPERTS + 1) * 4 + 8;  // ring + expert table
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4v __attribute__((ext_vector_type(4)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define LDS_AS __attribute__((address_space(3)))
 
 // Scheduling pattern for one k-step: MFMA, LDS read, MFMA, LDS read, ... then a fence.
@@ -105,19 +129,19 @@ struct TileDesc {
 // first stages of the next tile are requested before the current tile's epilogue, so they arrive
 // while the epilogue runs (no workgroup relaunch, no cold prologue per tile).
 template <int AT, int BT, bool DUAL, int EPI, bool RAGK>
-__global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
+__global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     static_assert(RAGK ? (AT == 1 && BT == 0) : (AT == 0), "operand forms");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     int32_t* t_off = reinterpret_cast<int32_t*>(smem + kStages * kStageBytes);  // [E+1] rows of each expert
     int32_t* t_pref = t_off + MOE_MAX_EXPERTS + 1;                              // [E+1] tiles before expert e
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 2, wn = wave & 3;  // 2 x 4 wavefronts, 128 x 64 each
+    const int wm = wave / kWN, wn = wave % kWN;  // 2 x kWN wavefronts, 128 rows x 32*NJ columns each
     const int n_out = DUAL ? TN / 2 : TN;     // output columns per tile
     const int n_tiles = (g.N + n_out - 1) / n_out;
     const int m_tiles_k = (g.M + TM - 1) / TM;  // ragged K only
 
     // ---- expert table in LDS: rows of each expert and the number of tiles before it ----
-    for (int i = threadIdx.x; i <= g.E; i += 512) t_off[i] = g.offsets[i];
+    for (int i = threadIdx.x; i <= g.E; i += kThreads) t_off[i] = g.offsets[i];
     __syncthreads();
     if (wave == 0) {  // exclusive scan of the per-expert tile counts: 4 experts per lane, then across lanes
         int c[4], sum = 0;
@@ -192,17 +216,19 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
     // ================= issue side: DMA loads of stream position p into ring buffer p & 3 =================
     const int64_t lda = g.lda, ldb = g.ldb;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
-    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 2048);
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * (CPW * 1024));
     // row form: chunk c = wave*2 + i covers rows 16c .. 16c+15; lane -> row 16c + lane/4, slot lane%4
     // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
     TileDesc di;                  // tile whose stages are being issued
     di.valid = false; di.e = 0; di.m0 = 0; di.m_lim = 0; di.n0 = 0; di.kbeg = 0; di.kend = 0; di.nk = 0;
-    uint32_t a_off[2], b_off[2];  // element offsets of this lane's 16-byte pieces (k-independent part)
-    bool b_second[2] = {false, false};
+    uint32_t a_off[CPW], b_off[CPW];  // element offsets of this lane's 16-byte pieces (k-independent part)
+    bool b_second[CPW];
     const bf16_t* iA[2];
     const bf16_t* iB[2];
     const bf16_t* iB2[2];
-    const int q_row[2] = {(wave * 2 + 0) * 2 + (lane >> 5), (wave * 2 + 1) * 2 + (lane >> 5)};
+    int q_row[CPW];  // k-row form: the k-row inside the stage of this lane's piece in chunk i
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) { q_row[i] = (wave * CPW + i) * 2 + (lane >> 5); b_second[i] = false; }
 
     auto setup_issue = [&]() {
 #pragma unroll
@@ -214,8 +240,8 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             iB2[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int c = wave * 2 + i;
+        for (int i = 0; i < CPW; ++i) {
+            const int c = wave * CPW + i;
             if constexpr (AT == 0) {
                 const int r = c * 16 + (lane >> 2);
                 int gr = di.m0 + r;
@@ -242,7 +268,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             }
         }
     };
-    // k-stage `stage` of tile di -> ring buffer `buf` (always exactly four DMA instructions per wavefront)
+    // k-stage `stage` of tile di -> ring buffer `buf` (always exactly 2*CPW DMA instructions per wavefront)
     auto issue = [&](int stage, int buf) {
         const int sg = stage >= di.nk ? 1 : 0;
         const int k0 = di.kbeg + (stage - sg * di.nk) * TK;
@@ -250,7 +276,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         const bf16_t* A = sg ? iA[1] : iA[0];
         const bf16_t* B = sg ? iB[1] : iB[0];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < CPW; ++i) {
             if constexpr (AT == 0) {
                 dma16(A + a_off[i] + k0, st + i * 1024);
             } else {
@@ -262,7 +288,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             }
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < CPW; ++i) {
             if constexpr (BT == 1) {
                 dma16(B + b_off[i] + k0, st + kBOff + i * 1024);
             } else {
@@ -283,7 +309,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
     const int tr_krow = (g16 >> 1) * 8 + (i16 >> 2);  // + kk*16 + t*4
     const int tr_sw = swz_krow(tr_krow);              // kk*16 + t*4 do not change the swizzle
     const int tr_lane_col = (g16 & 1) * 16 + (i16 & 3) * 4;
-    int a_rd[4], b_rd[2];  // byte offsets inside the operand tile, without the k-step term
+    int a_rd[4], b_rd[NJ];  // byte offsets inside the operand tile, without the k-step term
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if constexpr (AT == 0) {
@@ -294,8 +320,9 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         }
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int cb = DUAL ? (j * 128 + wn * 32) : (wn * 64 + j * 32);
+    for (int j = 0; j < NJ; ++j) {
+        // DUAL: blocks j < NJ/2 lie in the first matrix' half of the B tile, the others in the second
+        const int cb = DUAL ? ((j / (NJ / 2)) * 128 + wn * (NJ / 2) * 32 + (j % (NJ / 2)) * 32) : (wn * NJ * 32 + j * 32);
         if constexpr (BT == 1) {
             b_rd[j] = (cb + l32) * 64;
         } else {
@@ -305,11 +332,11 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
     }
     // fragments of k-step kk of a stage -> registers.  B first: the MFMAs below walk a[0] x b[0..1],
     // a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
-    auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+    auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[NJ]) {
         const char* sb = st + kBOff;
         const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < NJ; ++j) {
             if constexpr (BT == 1) {
                 b[j] = *reinterpret_cast<const bf16x8*>(sb + b_rd[j] + rowform);
             } else {
@@ -331,23 +358,24 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             }
         }
     };
-    f32x16 acc[4][2];
+    f32x16 acc[4][NJ];
     auto zero_acc = [&]() {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     };
-    auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
+    auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NJ]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     };
-    constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? 2 : 4);
+    constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? NJ : 2 * NJ);
+    constexpr int kPairs = kReads > 4 * NJ ? kReads : 4 * NJ;  // MFMA / LDS-read pairs to interleave per k-step
 
     // ---- epilogue of one tile.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
     // inside a 32x32 block) go through LDS, 64 rows at a time (block i of both wavefront rows), so that
@@ -357,7 +385,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
         {
             constexpr int PPR = 32;
-            for (int item = threadIdx.x; item < 256 * PPR; item += 512) {
+            for (int item = threadIdx.x; item < 256 * PPR; item += kThreads) {
                 const int row = t.m0 + item / PPR;
                 int col = (item % PPR) * 8;
                 bf16_t* dst = static_cast<bf16_t*>(g.C0);
@@ -382,8 +410,8 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                 for (int r = 0; r < 16; ++r) {
                     const int row = t.m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const int col = t.n0 + wn * 64 + j * 32 + l32;
+                    for (int j = 0; j < NJ; ++j) {
+                        const int col = t.n0 + wn * NJ * 32 + j * 32 + l32;
                         if (row < t.m_lim && col < g.N)
                             static_cast<float*>(g.C0)[cbase + (int64_t)row * g.ldc + col] = acc[i][j][r];
                     }
@@ -395,19 +423,21 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 for (int p = 0; p < 2; ++p) {
-                    if ((wn >> 1) == p) {
+                    {
 #pragma unroll
-                        for (int j = 0; j < 2; ++j)
+                        for (int j = 0; j < NJ; ++j)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
-                                const int col = (wn & 1) * 64 + j * 32 + l32;
+                                const int tcol = wn * NJ * 32 + j * 32 + l32;  // column inside the 256-wide tile
+                                const int col = tcol & 127;
                                 const int piece = (col >> 2) ^ (((sr >> 2) & 1) << 3);
-                                *reinterpret_cast<float*>(stg + sr * 512 + piece * 16 + (col & 3) * 4) = acc[i][j][r];
+                                if ((tcol >> 7) == p)
+                                    *reinterpret_cast<float*>(stg + sr * 512 + piece * 16 + (col & 3) * 4) = acc[i][j][r];
                             }
                     }
                     __syncthreads();
-                    for (int item = threadIdx.x; item < 64 * 16; item += 512) {
+                    for (int item = threadIdx.x; item < 64 * 16; item += kThreads) {
                         const int sr = item >> 4, cg = item & 15;
                         const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
                         if (grow < t.m_lim && gcol < g.N) {
@@ -444,17 +474,31 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                 }
             }
         } else {
-            // bf16 tiles: stage [64 rows][ROWB bytes], piece index XORed with 8*((row>>2)&1), then 16 bytes
-            // per lane along rows.
+            // bf16 tiles: stage [64 rows][ROWB bytes] with swizzled 16-byte pieces, then 16 bytes per lane along rows.
             constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
             constexpr int PPR = ROWB / 16;  // pieces per row
-            auto put = [&](int sr, int col, float v) {
-                const int piece = (col >> 3) ^ (((sr >> 2) & 1) << 3);
-                *reinterpret_cast<bf16_t*>(stg + sr * ROWB + piece * 16 + (col & 7) * 2) = f32_to_bf16(v);
+            // Two accumulators of a lane that sit in consecutive rows (r0 = 2m, r0+1) are traded with the
+            // neighbouring lane (next column): the even lane ends up with row r0, columns (c, c+1), the odd
+            // lane with row r0+1, columns (c-1, c).  One packed conversion and one 4-byte LDS write per pair.
+            // Staging swizzle: piece ^ (8*((row>>2)&1) + 4*(row&1)) keeps the four lane groups of a write
+            // (even/odd lanes, lower/upper half of the wavefront) on different banks.
+            const bool odd = (lane & 1) != 0;
+            auto stg_sw = [](int sr) { return (((sr >> 2) & 1) << 3) | ((sr & 1) << 2); };
+            auto put2 = [&](int r0, int colbase, float v0, float v1) {
+                const float send = odd ? v0 : v1;
+                const float recv = __builtin_bit_cast(
+                    float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, send), 0xB1, 0xf, 0xf, true));  // quad_perm [1,0,3,2]
+                f32x2v pr;
+                pr[0] = odd ? recv : v0;
+                pr[1] = odd ? v1 : recv;
+                const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
+                const int sr = wm * 32 + (r0 >> 2) * 8 + kg * 4 + (r0 & 3) + (odd ? 1 : 0);
+                const int col = colbase + (l32 & ~1);
+                *reinterpret_cast<bf16x2*>(stg + sr * ROWB + (((col >> 3) ^ stg_sw(sr)) << 4) + (col & 7) * 2) = pk;
             };
             auto flush = [&](int i, bf16_t* dst0, bf16_t* dst1, int cols0) {
                 __syncthreads();
-                for (int item = threadIdx.x; item < 64 * PPR; item += 512) {
+                for (int item = threadIdx.x; item < 64 * PPR; item += kThreads) {
                     const int sr = item / PPR, pc = item - sr * PPR;
                     const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
                     int col = pc * 8;
@@ -463,7 +507,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                     const int gcol = t.n0 + col;
                     if (grow < t.m_lim && gcol < g.N)
                         *reinterpret_cast<u32x4*>(dst + cbase + (int64_t)grow * g.ldc + gcol) =
-                            *reinterpret_cast<const u32x4*>(stg + sr * ROWB + ((pc ^ (((sr >> 2) & 1) << 3)) << 4));
+                            *reinterpret_cast<const u32x4*>(stg + sr * ROWB + ((pc ^ stg_sw(sr)) << 4));
                 }
                 __syncthreads();
             };
@@ -472,31 +516,36 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
                 if constexpr (EPI == EPI_SWIGLU) {
                     for (int pass = 0; pass < (g.S0 ? 3 : 1); ++pass) {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
-                            const float a = acc[i][0][r], b = acc[i][1][r];
-                            put(sr, wn * 32 + l32, pass == 0 ? silu_f(a) * b : pass == 1 ? a : b);
-                        }
+                        for (int j = 0; j < NJ / 2; ++j)
+#pragma unroll
+                            for (int r = 0; r < 16; r += 2) {
+                                float v[2];
+#pragma unroll
+                                for (int z = 0; z < 2; ++z) {
+                                    const float a = acc[i][j][r + z], b = acc[i][j + NJ / 2][r + z];
+                                    v[z] = pass == 0 ? silu_f(a) * b : pass == 1 ? a : b;
+                                }
+                                put2(r, wn * (NJ / 2) * 32 + j * 32, v[0], v[1]);
+                            }
                         bf16_t* dst = pass == 0 ? static_cast<bf16_t*>(g.C0)
                                                 : const_cast<bf16_t*>(static_cast<const bf16_t*>(pass == 1 ? g.S0 : g.S1));
                         flush(i, dst, nullptr, 0);
                     }
                 } else if constexpr (DUAL) {  // EPI_STORE2: first 128 columns -> C0, second 128 -> C1
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
-                        put(sr, wn * 32 + l32, acc[i][0][r]);
-                        put(sr, 128 + wn * 32 + l32, acc[i][1][r]);
-                    }
+                    for (int j = 0; j < NJ / 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; r += 2) {
+                            put2(r, wn * (NJ / 2) * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1]);
+                            put2(r, 128 + wn * (NJ / 2) * 32 + j * 32, acc[i][j + NJ / 2][r], acc[i][j + NJ / 2][r + 1]);
+                        }
                     flush(i, static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
                 } else {  // EPI_STORE
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                    for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
-                            put(sr, wn * 64 + j * 32 + l32, acc[i][j][r]);
-                        }
+                        for (int r = 0; r < 16; r += 2)
+                            put2(r, wn * NJ * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1]);
                     flush(i, static_cast<bf16_t*>(g.C0), nullptr, 0);
                 }
             }
@@ -507,10 +556,10 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
     // Per tile: stages 0..3 are in flight when its loop starts (stages 0..2 were issued before the
     // previous tile's epilogue, stage 3 after it); the barrier in the middle of iteration `it`
     // publishes stage it+1 and frees the buffer of stage it, into which stage it+4 is issued at once.
-    bf16x8 fa[2][4], fb[2][2];
+    bf16x8 fa[2][4], fb[2][NJ];
     auto wait_loads = [&](int stages_allowed) {  // at most that many of the youngest stage loads may be pending
-        if (stages_allowed >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if (stages_allowed == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (stages_allowed >= 2) asm volatile(MOE_VMCNT(MOE_VM2) ::: "memory");
+        else if (stages_allowed == 1) asm volatile(MOE_VMCNT(MOE_VM1) ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
     int round = 0;
@@ -530,7 +579,7 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
         const int total = t.nk * g.nseg;
         zero_acc();
         // stage 0 must have landed: it is followed by min(total, 4) - 1 younger stage loads
-        if (total >= 4) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        if (total >= 4) asm volatile(MOE_VMCNT(MOE_VM3) ::: "memory");
         else wait_loads(total - 1);
         __syncthreads();
         load_frags(smem, 0, fa[0], fb[0]);
@@ -541,15 +590,15 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
             load_frags(st, 1, fa[1], fb[1]);
             mma(fa[0], fb[0]);
-            interleave_mfma_dsread<kReads>();
+            interleave_mfma_dsread<kPairs>();
             // this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
-            // (the eight youngest loads belong to stages it+2 and it+3)
-            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            // (the youngest 4*CPW loads belong to stages it+2 and it+3)
+            asm volatile(MOE_VMCNT(MOE_VM2) " lgkmcnt(0)" ::: "memory");
             __syncthreads();
             issue(it + kStages, it & (kStages - 1));
             load_frags(nx, 0, fa[0], fb[0]);
             mma(fa[1], fb[1]);
-            interleave_mfma_dsread<kReads>();
+            interleave_mfma_dsread<kPairs>();
         }
         // ---- the last (up to four) stages: nothing left to issue for this tile ----
         for (; it < total; ++it) {
@@ -557,14 +606,14 @@ __global__ __launch_bounds__(512) void gg256_kernel(const GArgs g) {
             const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
             load_frags(st, 1, fa[1], fb[1]);
             mma(fa[0], fb[0]);
-            interleave_mfma_dsread<kReads>();
+            interleave_mfma_dsread<kPairs>();
             const int rem = total - 1 - it;  // stages after this one, all issued already
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             wait_loads(rem - 1);
             __syncthreads();
             if (rem > 0) load_frags(nx, 0, fa[0], fb[0]);
             mma(fa[1], fb[1]);
-            interleave_mfma_dsread<kReads>();
+            interleave_mfma_dsread<kPairs>();
         }
         // ---- next tile: its first stages are requested before this tile's epilogue ----
         // (every DMA load of this tile has landed and every wavefront is past the last barrier, after

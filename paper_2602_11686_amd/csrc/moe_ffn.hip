@@ -363,7 +363,7 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
                     attr_done = true;
                 }
                 (void)R;
-                kern<<<dim3(256), 512, kGemmLds, st>>>(g);  // persistent: one workgroup per CU
+                kern<<<dim3(256), kThreads, kGemmLds, st>>>(g);  // persistent: one workgroup per CU
                 return;
             }
         }
@@ -400,7 +400,7 @@ void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, c
                                   kGemmLds);
         attr_done = true;
     }
-    kern<<<dim3(256), 512, kGemmLds, st>>>(g);
+    kern<<<dim3(256), kThreads, kGemmLds, st>>>(g);
 }
 
 size_t ffn_fwd_workspace_bytes(const moe_shape* s) {

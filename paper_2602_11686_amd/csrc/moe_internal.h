@@ -66,9 +66,12 @@ template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
-__device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)); }
+// silu and its derivative with the hardware exp2 / reciprocal (about 1 ulp each): these run on
+// 128 accumulators per lane in the GEMM epilogues, where a full-precision division is what costs.
+__device__ __forceinline__ float sigmoid_f(float a) { return __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
+__device__ __forceinline__ float silu_f(float a) { return a * sigmoid_f(a); }
 __device__ __forceinline__ float silu_grad_f(float a) {
-    float s = 1.0f / (1.0f + __expf(-a));
+    const float s = sigmoid_f(a);
     return s * (1.0f + a * (1.0f - s));
 }
 
