@@ -374,6 +374,18 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             for (int j = 0; j < NJ; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     };
+    // The accumulators as operands of an empty volatile asm: every MFMA issued so far stays in front of
+    // the waits and the barrier that follow (instruction selection otherwise moves most of a k-step's
+    // MFMAs behind the barrier, which then drains the matrix pipe while the wavefronts wait).
+    auto pin_acc = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                if constexpr (kWaves == 8) asm volatile("" : "+v"(acc[i][j]));  // 256 registers per lane: all of them VGPRs
+                else asm volatile("" : "+a"(acc[i][j]));                        // 512: accumulators in AGPRs
+            }
+    };
     constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? NJ : 2 * NJ);
     constexpr int kPairs = kReads > 4 * NJ ? kReads : 4 * NJ;  // MFMA / LDS-read pairs to interleave per k-step
 
@@ -591,6 +603,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             load_frags(st, 1, fa[1], fb[1]);
             mma(fa[0], fb[0]);
             interleave_mfma_dsread<kPairs>();
+            pin_acc();
             // this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
             // (the youngest 4*CPW loads belong to stages it+2 and it+3)
             asm volatile(MOE_VMCNT(MOE_VM2) " lgkmcnt(0)" ::: "memory");
@@ -608,6 +621,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             mma(fa[0], fb[0]);
             interleave_mfma_dsread<kPairs>();
             const int rem = total - 1 - it;  // stages after this one, all issued already
+            pin_acc();
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             wait_loads(rem - 1);
             __syncthreads();
