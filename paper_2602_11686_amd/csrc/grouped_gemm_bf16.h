@@ -268,8 +268,9 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
         }
     };
-    // k-stage `stage` of tile di -> ring buffer `buf` (always exactly 2*CPW DMA instructions per wavefront)
-    auto issue = [&](int stage, int buf) {
+    // k-stage `stage` of tile di -> ring buffer `buf`: always exactly 2*CPW DMA instructions per wavefront,
+    // numbered idx = 0 .. 2*CPW-1 (A chunks first); issue_part issues the idx range [lo, hi).
+    auto issue_part = [&](int stage, int buf, int lo, int hi) {
         const int sg = stage >= di.nk ? 1 : 0;
         const int k0 = di.kbeg + (stage - sg * di.nk) * TK;
         const uint32_t st = lds_wave + buf * kStageBytes;
@@ -277,6 +278,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         const bf16_t* B = sg ? iB[1] : iB[0];
 #pragma unroll
         for (int i = 0; i < CPW; ++i) {
+            if (i < lo || i >= hi) continue;
             if constexpr (AT == 0) {
                 dma16(A + a_off[i] + k0, st + i * 1024);
             } else {
@@ -289,6 +291,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         }
 #pragma unroll
         for (int i = 0; i < CPW; ++i) {
+            if (CPW + i < lo || CPW + i >= hi) continue;
             if constexpr (BT == 1) {
                 dma16(B + b_off[i] + k0, st + kBOff + i * 1024);
             } else {
@@ -300,6 +303,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
         }
     };
+    auto issue = [&](int stage, int buf) { issue_part(stage, buf, 0, 2 * CPW); };
 
     // ================= compute side =================
     const int l32 = lane & 31, kg = lane >> 5;
@@ -377,14 +381,15 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     // The accumulators as operands of an empty volatile asm: every MFMA issued so far stays in front of
     // the waits and the barrier that follow (instruction selection otherwise moves most of a k-step's
     // MFMAs behind the barrier, which then drains the matrix pipe while the wavefronts wait).
+    auto pin_one = [](f32x16& v) {
+        if constexpr (kWaves == 8) asm volatile("" : "+v"(v));  // 256 registers per lane: all of them VGPRs
+        else asm volatile("" : "+a"(v));                        // 512: accumulators in AGPRs
+    };
     auto pin_acc = [&]() {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                if constexpr (kWaves == 8) asm volatile("" : "+v"(acc[i][j]));  // 256 registers per lane: all of them VGPRs
-                else asm volatile("" : "+a"(acc[i][j]));                        // 512: accumulators in AGPRs
-            }
+            for (int j = 0; j < NJ; ++j) pin_one(acc[i][j]);
     };
     constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? NJ : 2 * NJ);
     constexpr int kPairs = kReads > 4 * NJ ? kReads : 4 * NJ;  // MFMA / LDS-read pairs to interleave per k-step
@@ -608,10 +613,20 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             // (the youngest 4*CPW loads belong to stages it+2 and it+3)
             asm volatile(MOE_VMCNT(MOE_VM2) " lgkmcnt(0)" ::: "memory");
             __syncthreads();
-            issue(it + kStages, it & (kStages - 1));
+            // second k-step: the DMA instructions of stage it+4 (and their address arithmetic) are dealt out
+            // between the MFMAs, a quarter after each row of MFMA blocks, so that the matrix pipe stays fed
+            // while they issue; the pins keep each row of MFMAs in front of its quarter.
             load_frags(nx, 0, fa[0], fb[0]);
-            mma(fa[1], fb[1]);
-            interleave_mfma_dsread<kPairs>();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+                    pin_one(acc[i][j]);
+                }
+                issue_part(it + kStages, it & (kStages - 1), i * (CPW / 2), (i + 1) * (CPW / 2));
+                if (i < 3) pin_one(acc[i + 1][0]);  // the next row's MFMAs read this value: they stay behind the DMA
+            }
         }
         // ---- the last (up to four) stages: nothing left to issue for this tile ----
         for (; it < total; ++it) {
