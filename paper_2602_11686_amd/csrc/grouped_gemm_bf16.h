@@ -89,6 +89,13 @@ __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_addr) {
                  : "memory", "m0");
 }
 
+// The same with the address split into a wave-uniform 64-bit base (SGPR pair) and a per-lane 32-bit byte
+// offset (kept below 2^31): nothing but a scalar add is needed to move the base from one k-stage to the next.
+__device__ __forceinline__ void dma16_s(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+
 // Walk of the n-tiles x m-tiles grid of one expert: n-tiles in super-columns of kSuperN,
 // m-tiles next, the n-tiles of the super-column fastest.  32 consecutive tiles (what one
 // XCD runs at a time) then form a block of 8 m-tiles x 4 n-tiles (or all m-tiles x more
@@ -221,7 +228,13 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
     TileDesc di;                  // tile whose stages are being issued
     di.valid = false; di.e = 0; di.m0 = 0; di.m_lim = 0; di.n0 = 0; di.kbeg = 0; di.kend = 0; di.nk = 0;
-    uint32_t a_off[CPW], b_off[CPW];  // element offsets of this lane's 16-byte pieces (k-independent part)
+    // Ragged M: per-lane byte offsets of this lane's 16-byte pieces relative to a wave-uniform base of the tile
+    // (sA / sB per K segment; pB for the two-matrix B tile, whose lanes read from two allocations).
+    // Ragged K: element offsets (k-independent part), full addresses are formed per load.
+    uint32_t a_off[CPW], b_off[CPW];
+    const char* sA[2];
+    const char* sB[2];
+    const bf16_t* pB[2][CPW];
     bool b_second[CPW];
     const bf16_t* iA[2];
     const bf16_t* iB[2];
@@ -240,13 +253,19 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             iB2[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;
         }
 #pragma unroll
+        for (int sgi = 0; sgi < 2; ++sgi) {
+            if constexpr (AT == 0) sA[sgi] = reinterpret_cast<const char*>(iA[sgi] + (int64_t)di.m0 * lda);
+            if constexpr (BT == 1) sB[sgi] = reinterpret_cast<const char*>(iB[sgi] + (int64_t)di.n0 * ldb);
+            else sB[sgi] = reinterpret_cast<const char*>(iB[sgi] + di.n0);
+        }
+#pragma unroll
         for (int i = 0; i < CPW; ++i) {
             const int c = wave * CPW + i;
             if constexpr (AT == 0) {
                 const int r = c * 16 + (lane >> 2);
-                int gr = di.m0 + r;
-                gr = gr < di.m_lim ? gr : di.m_lim - 1;  // rows past the expert's end: any valid row (masked at the store)
-                a_off[i] = (uint32_t)gr * (uint32_t)lda + ((lane & 3) ^ swz_rows(r)) * 8;
+                const int last = di.m_lim - 1 - di.m0;  // rows past the expert's end: any valid row (masked at the store)
+                const int rl = r < last ? r : last;
+                a_off[i] = ((uint32_t)rl * (uint32_t)lda + ((lane & 3) ^ swz_rows(r)) * 8) * 2;
             } else {
                 int col = di.m0 + ((lane & 31) ^ swz_krow(q_row[i])) * 8;
                 col = col < g.M ? col : g.M - 8;
@@ -254,17 +273,25 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
             if constexpr (BT == 1) {
                 const int r = c * 16 + (lane >> 2);
-                int gn = di.n0 + r;
-                gn = gn < g.N ? gn : g.N - 1;
-                b_off[i] = (uint32_t)gn * (uint32_t)ldb + ((lane & 3) ^ swz_rows(r)) * 8;
+                const int last = g.N - 1 - di.n0;
+                const int rl = r < last ? r : last;
+                b_off[i] = ((uint32_t)rl * (uint32_t)ldb + ((lane & 3) ^ swz_rows(r)) * 8) * 2;
             } else {
                 const int piece = (lane & 31) ^ swz_krow(q_row[i]);
                 int col;
                 if constexpr (DUAL) col = di.n0 + (piece & 15) * 8;  // pieces 16..31 come from the second matrix
                 else col = di.n0 + piece * 8;
                 col = col < g.N ? col : g.N - 8;
-                b_off[i] = col;
-                if constexpr (DUAL) b_second[i] = (piece >> 4) != 0;
+                if constexpr (RAGK) {
+                    b_off[i] = col;
+                    if constexpr (DUAL) b_second[i] = (piece >> 4) != 0;
+                } else if constexpr (DUAL) {
+#pragma unroll
+                    for (int sgi = 0; sgi < 2; ++sgi)
+                        pB[sgi][i] = ((piece >> 4) != 0 ? iB2[sgi] : iB[sgi]) + (int64_t)q_row[i] * ldb + col;
+                } else {
+                    b_off[i] = ((uint32_t)q_row[i] * (uint32_t)ldb + (uint32_t)(col - di.n0)) * 2;
+                }
             }
         }
     };
@@ -274,29 +301,37 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         const int sg = stage >= di.nk ? 1 : 0;
         const int k0 = di.kbeg + (stage - sg * di.nk) * TK;
         const uint32_t st = lds_wave + buf * kStageBytes;
-        const bf16_t* A = sg ? iA[1] : iA[0];
-        const bf16_t* B = sg ? iB[1] : iB[0];
+        if constexpr (!RAGK) {
+            const char* Ab = (sg ? sA[1] : sA[0]) + (int64_t)k0 * 2;
+            const char* Bb = (sg ? sB[1] : sB[0]) + (BT == 1 ? (int64_t)k0 * 2 : (int64_t)k0 * ldb * 2);
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) {
-            if (i < lo || i >= hi) continue;
-            if constexpr (AT == 0) {
-                dma16(A + a_off[i] + k0, st + i * 1024);
-            } else {
+            for (int i = 0; i < CPW; ++i) {
+                if (i < lo || i >= hi) continue;
+                dma16_s(Ab, a_off[i], st + i * 1024);
+            }
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                if (CPW + i < lo || CPW + i >= hi) continue;
+                if constexpr (BT == 0 && DUAL) dma16((sg ? pB[1][i] : pB[0][i]) + (int64_t)k0 * ldb, st + kBOff + i * 1024);
+                else dma16_s(Bb, b_off[i], st + kBOff + i * 1024);
+            }
+        } else {
+            const bf16_t* A = sg ? iA[1] : iA[0];
+            const bf16_t* B = sg ? iB[1] : iB[0];
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                if (i < lo || i >= hi) continue;
                 // k-rows past the expert's rows read a row of zeros: they add nothing to the sums
                 const int kr = k0 + q_row[i];
                 const bf16_t* src = kr < di.kend ? A + (int64_t)kr * lda + a_off[i]
                                                  : static_cast<const bf16_t*>(g.zero_row) + (lane & 31) * 8;
                 dma16(src, st + i * 1024);
             }
-        }
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) {
-            if (CPW + i < lo || CPW + i >= hi) continue;
-            if constexpr (BT == 1) {
-                dma16(B + b_off[i] + k0, st + kBOff + i * 1024);
-            } else {
+            for (int i = 0; i < CPW; ++i) {
+                if (CPW + i < lo || CPW + i >= hi) continue;
                 int kr = k0 + q_row[i];
-                if constexpr (RAGK) kr = kr < di.kend ? kr : di.kend - 1;  // any valid (finite) row: it meets zeros
+                kr = kr < di.kend ? kr : di.kend - 1;  // any valid (finite) row: it meets zeros
                 const bf16_t* src = B;
                 if constexpr (DUAL) src = b_second[i] ? (sg ? iB2[1] : iB2[0]) : B;
                 dma16(src + (int64_t)kr * ldb + b_off[i], st + kBOff + i * 1024);

@@ -351,8 +351,8 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
     if (s->dtype == MOE_BF16) {
         constexpr bool fast_form = RAGK ? (AT == 1 && BT == 0) : (AT == 0);
         if constexpr (fast_form) {
-            // (the kernel keeps per-lane element offsets in 32 bits)
-            const bool ok = g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8 &&
+            // (the kernel keeps per-lane offsets in 32 bits; inside a tile they stay below 2^31 bytes)
+            const bool ok = g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8 && g.lda < (1 << 21) && g.ldb < (1 << 21) &&
                             (uint64_t)R * (uint64_t)g.lda < (1ull << 32) && (uint64_t)g.N * (uint64_t)g.ldb < (1ull << 32) &&
                             (RAGK ? (g.M >= 8) : (g.K % TK == 0));
             if (ok) {
