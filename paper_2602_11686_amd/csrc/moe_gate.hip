@@ -177,19 +177,20 @@ __device__ __forceinline__ float wave_max_f32(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
-template <int NT>  // expert tiles of 32
-__global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wgT,
+template <int NT, int NW>  // expert tiles of 32; wavefronts (the contraction is split NW ways)
+__global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wgT,
                                                              const float* __restrict__ bias, int32_t* __restrict__ ids,
                                                              float* __restrict__ wout, float* __restrict__ logits_out,
                                                              int Tn, int d, int E, int k) {
-    extern __shared__ float part[];  // [4][32][NT*32] partial logits, then the picked logits [4][8][MOE_MAX_EXPERTS]
+    extern __shared__ float part[];  // [NW][32][NT*32] partial logits, then the picked logits [32][MOE_MAX_EXPERTS]
+    constexpr int TPW = kGateMT / NW;  // tokens finished by each wavefront
     constexpr int EP = NT * 32;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, kg = lane >> 5;
     const int t0 = blockIdx.x * kGateMT;
     int trow = t0 + l32;
     trow = trow < Tn ? trow : Tn - 1;
-    const int kq = d / 4;
+    const int kq = d / NW;
     const bf16_t* xa = x + (size_t)trow * d + wave * kq + kg * 32;
     const bf16_t* wb = wgT + (size_t)l32 * d + wave * kq + kg * 32;
 
@@ -236,18 +237,19 @@ __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __res
             mine[row * EP + j * 32 + l32] = acc[j][r];
         }
     __syncthreads();
-    // wave w finishes tokens 8w .. 8w+7; lane owns experts lane, lane+64, ...
-    float vals[8][kGateMaxNE];
+    // wave w finishes tokens TPW*w .. TPW*w + TPW-1; lane owns experts lane, lane+64, ...
+    float vals[TPW][kGateMaxNE];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = wave * 8 + i;
+    for (int i = 0; i < TPW; ++i) {
+        const int row = wave * TPW + i;
 #pragma unroll
         for (int j = 0; j < kGateMaxNE; ++j) {
             const int e = lane + 64 * j;
             float v = -INFINITY;
             if (e < E) {
-                v = ((part[(0 * kGateMT + row) * EP + e] + part[(1 * kGateMT + row) * EP + e]) +
-                     part[(2 * kGateMT + row) * EP + e]) + part[(3 * kGateMT + row) * EP + e];
+                v = part[row * EP + e];
+#pragma unroll
+                for (int q = 1; q < NW; ++q) v += part[(q * kGateMT + row) * EP + e];  // fixed order
                 v += bias ? bias[e] : 0.f;
             }
             vals[i][j] = v;
@@ -255,11 +257,11 @@ __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __res
     }
     __syncthreads();  // partial sums consumed; LDS is reused for the picked logits
     // top-k of the wave's 8 tokens, all 8 arg-max reductions of a round in flight together
-    float* sel = part + wave * 8 * MOE_MAX_EXPERTS;  // [8][k]
+    float* sel = part + wave * TPW * MOE_MAX_EXPERTS;  // [TPW][k]
     if (logits_out) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int t = t0 + wave * 8 + i;
+        for (int i = 0; i < TPW; ++i) {
+            const int t = t0 + wave * TPW + i;
 #pragma unroll
             for (int j = 0; j < kGateMaxNE; ++j)
                 if (t < Tn && lane + 64 * j < E) logits_out[(size_t)t * E + lane + 64 * j] = vals[i][j];
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __res
     }
     for (int s = 0; s < k; ++s) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < TPW; ++i) {
             float lv = vals[i][0];
 #pragma unroll
             for (int j = 1; j < kGateMaxNE; ++j) lv = fmaxf(lv, vals[i][j]);
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __res
                 for (int j = 0; j < kGateMaxNE; ++j)
                     if (be == lane + 64 * j) vals[i][j] = -INFINITY;
             }
-            const int t = t0 + wave * 8 + i;
+            const int t = t0 + wave * TPW + i;
             if (lane == 0 && t < Tn) {
                 ids[(size_t)t * k + s] = be;
                 sel[i * MOE_MAX_EXPERTS + s] = m;
@@ -293,8 +295,8 @@ __global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const bf16_t* __res
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int t = t0 + wave * 8 + i;
+    for (int i = 0; i < TPW; ++i) {
+        const int t = t0 + wave * TPW + i;
         if (t >= Tn) continue;
         const float* sl = sel + i * MOE_MAX_EXPERTS;
         const float m0 = sl[0];
@@ -486,20 +488,27 @@ extern "C" moe_status moe_gate_topk(const moe_shape* s, const void* x, const voi
         bf16_t* wgT = static_cast<bf16_t*>(ws);
         gate_transpose_bf16_kernel<<<256, 256, 0, st>>>(static_cast<const bf16_t*>(w_gate), wgT, s->d, s->E, NT * 32);
         const int grid = (s->T + kGateMT - 1) / kGateMT;
-        size_t lds = (size_t)4 * kGateMT * NT * 32 * sizeof(float);            // partial logits
-        if (lds < (size_t)4 * 8 * MOE_MAX_EXPERTS * sizeof(float)) lds = (size_t)4 * 8 * MOE_MAX_EXPERTS * sizeof(float);
-#define MOE_GATE_LAUNCH(N)                                                                                         \
+        // 8 wavefronts (the contraction split 8 ways) halve the chain of dependent loads of a 32-token tile;
+        // the partial logits of 8 wavefronts fit the LDS up to 128 padded experts.
+        const int NW = (s->d % 512 == 0 && NT <= 4) ? 8 : 4;
+        size_t lds = (size_t)NW * kGateMT * NT * 32 * sizeof(float);            // partial logits
+        if (lds < (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float)) lds = (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float);
+#define MOE_GATE_LAUNCH(N, W)                                                                                      \
     {                                                                                                              \
         static bool attr = false;                                                                                  \
         if (!attr) {                                                                                               \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_topk_mfma_kernel<N>),                    \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_topk_mfma_kernel<N, W>),                 \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGateMT * 256 * 4);          \
             attr = true;                                                                                           \
         }                                                                                                          \
-        gate_topk_mfma_kernel<N><<<grid, 256, lds, st>>>(static_cast<const bf16_t*>(x), wgT, bias, topk_ids, topk_w, \
-                                                         logits_out, s->T, s->d, s->E, s->k);                      \
+        gate_topk_mfma_kernel<N, W><<<grid, W * 64, lds, st>>>(static_cast<const bf16_t*>(x), wgT, bias, topk_ids, \
+                                                               topk_w, logits_out, s->T, s->d, s->E, s->k);        \
     }
-        if (NT == 1) MOE_GATE_LAUNCH(1) else if (NT == 2) MOE_GATE_LAUNCH(2) else if (NT == 4) MOE_GATE_LAUNCH(4) else MOE_GATE_LAUNCH(8)
+        if (NW == 8) {
+            if (NT == 1) MOE_GATE_LAUNCH(1, 8) else if (NT == 2) MOE_GATE_LAUNCH(2, 8) else MOE_GATE_LAUNCH(4, 8)
+        } else {
+            if (NT == 1) MOE_GATE_LAUNCH(1, 4) else if (NT == 2) MOE_GATE_LAUNCH(2, 4) else if (NT == 4) MOE_GATE_LAUNCH(4, 4) else MOE_GATE_LAUNCH(8, 4)
+        }
 #undef MOE_GATE_LAUNCH
         return launch_status(who);
     }
