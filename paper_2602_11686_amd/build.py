@@ -16,6 +16,8 @@ LIB = os.path.join(HERE, "libmoe.so")
 OBJ = os.path.join(HERE, "_build")
 
 SOURCES = ["moe_api.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip"]
+HOST_SOURCES = ["moe_planner.cpp"]  # host-only C++ (the CPU planner), compiled with g++
+HOST_FLAGS = ["-O2", "-fPIC", "-std=c++17", "-ffp-contract=off", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
          # packed fp32 VALU forms are kept out of the generated code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -39,8 +41,20 @@ def build(verbose: bool = False) -> str:
             sys.stderr.write(r.stderr)
         return obj
 
+    def host_one(src):
+        obj = os.path.join(OBJ, src.replace(".cpp", ".o"))
+        cmd = [os.environ.get("CXX", "g++"), *HOST_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            sys.stderr.write(r.stdout + r.stderr)
+            raise RuntimeError(f"g++ failed on {src}")
+        return obj
+
     with ThreadPoolExecutor(4) as ex:
         objs = list(ex.map(one, SOURCES))
+    objs += [host_one(src) for src in HOST_SOURCES]
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
     return LIB

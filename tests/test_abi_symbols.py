@@ -8,8 +8,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+def declared_functions(header="moe.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
 
@@ -29,6 +29,10 @@ def test_library_exports_every_declared_symbol():
     for n in declared_functions():
         assert hasattr(L, n), n
     assert sorted(B.EXPORTS) == declared_functions()
+    from paper_2602_11686_amd import planner
+    for n in declared_functions("moe_planner.h"):
+        assert hasattr(L, n), n
+    assert sorted(planner.PLANNER_EXPORTS) == declared_functions("moe_planner.h")
 
 
 def test_host_side_validation_needs_no_gpu():
