@@ -121,6 +121,41 @@ moe_status moe_grouped_ffn_fwd(const moe_shape* shape, const void* x_perm, const
                                void* y_perm /*[R,d] el*/, void* a_save, void* b_save, void* ws,
                                size_t ws_bytes, void* stream);
 
+/* The token dispatcher of one device: the lite routing of the paper's appendix (Lite Routing
+ * Algorithm) folded into the permutation.  Experts may be replicated; a replica slot is a "group"
+ * g in [0, G), G <= MOE_MAX_EXPERTS, numbered so that the groups of one destination device are
+ * consecutive (the caller - the planner - numbers them; see moe_plan_dispatch_table).  For expert e
+ * the sending device may use the groups rep_group[rep_begin[e] .. rep_begin[e+1]) (its node's replicas
+ * if there are any, else all).  The n_e pairs of expert e, in stable order (ascending p), are cut into
+ * len = rep_begin[e+1] - rep_begin[e] consecutive blocks of n_e / len pairs, the first n_e % len
+ * blocks one pair longer; block r belongs to group rep_group[rep_begin[e] + r].
+ *   expert_counts[e] = n_e;   group_counts[g] = pairs of group g (0 for groups not listed);
+ *   group_offsets = exclusive prefix sum of group_counts, group_offsets[G] = R;
+ *   row_of_pair[p] = group_offsets[g(p)] + (position of p inside its block); pair_of_row = inverse;
+ *   x_perm[row_of_pair[p], :] = x[p / k, :].
+ * Rows are therefore ordered by group: one contiguous send region per destination device.
+ * rep_begin, rep_group are DEVICE arrays and are checked on the device (list bounds against n_rep,
+ * a list for every expert that has pairs, group ids inside [0, G), no group listed twice).  If a check
+ * fails, *table_errors (device, may be NULL) receives a non-zero bit mask, every pair is counted in
+ * group 0 and the rows are in plain expert order: no index ever leaves [0, R).  A valid table writes 0.
+ * x_perm may be NULL.  Workspace: used. */
+moe_status moe_permute_lite(const moe_shape* shape, int32_t G, int32_t n_rep, const void* x,
+                            const int32_t* topk_ids, const int32_t* rep_begin /*[E+1]*/,
+                            const int32_t* rep_group /*[n_rep]*/, int32_t* expert_counts /*[E]*/,
+                            int32_t* group_counts /*[G]*/, int32_t* group_offsets /*[G+1]*/,
+                            int32_t* row_of_pair /*[R]*/, int32_t* pair_of_row /*[R]*/,
+                            void* x_perm /*[R,d] el or NULL*/, int32_t* table_errors /*[1] or NULL*/,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* moe_grouped_ffn_fwd over replica groups: the rows [group_offsets[g], group_offsets[g+1]) are
+ * multiplied with the weights of expert expert_of_group[g] (DEVICE array [G]; entries are clamped
+ * into [0, E-1]).  Replicas of one expert share its weights, so with the rows of moe_permute_lite
+ * the layer output equals that of the plain path bit for bit.  Everything else as moe_grouped_ffn_fwd. */
+moe_status moe_grouped_ffn_fwd_groups(const moe_shape* shape, int32_t G, const int32_t* expert_of_group,
+                                      const void* x_perm, const int32_t* group_offsets, const void* w1,
+                                      const void* w3, const void* w2, void* y_perm, void* a_save,
+                                      void* b_save, void* ws, size_t ws_bytes, void* stream);
+
 /* Expert computation, backward (section 3.2 prices it at twice the forward).
  *   dH = dy_perm * w2[e]^T,  dA = dH (.) B (.) silu'(A),  dB = dH (.) silu(A)
  *   dx_perm = dA * w1[e]^T + dB * w3[e]^T

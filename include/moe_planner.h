@@ -89,6 +89,16 @@ moe_status moe_plan_time_cost(const moe_plan_shape* s, const moe_plan_cost* c, c
 moe_status moe_plan_expert_layout(const moe_plan_shape* s, const moe_plan_cost* c, const int64_t* R, int32_t eps,
                                   uint64_t seed, int32_t* A, double* T, int32_t* best_index, int32_t* replicas_set);
 
+/* The table the token dispatcher of device `rank` needs (moe_permute_lite, moe_grouped_ffn_fwd_groups):
+ * groups = replica slots numbered by (device, expert index on that device, copy); G = sum of A.
+ *   expert_of_group[g], device_of_group[g]   (capacity N*C each)
+ *   rep_begin[E+1], rep_group[<= N*C]: for expert j the groups `rank` routes to, ascending - the replicas
+ *   inside rank's node if it has any, else all replicas (appendix, lite routing algorithm).
+ * *G_out and *n_rep_out receive G and rep_begin[E]. */
+moe_status moe_plan_dispatch_table(const moe_plan_shape* s, const int32_t* A, int32_t rank, int32_t* G_out,
+                                   int32_t* n_rep_out, int32_t* expert_of_group, int32_t* device_of_group,
+                                   int32_t* rep_begin, int32_t* rep_group);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = [
     "moe_status_string", "moe_last_error", "moe_abi_version", "moe_workspace_bytes", "moe_gate_topk",
     "moe_permute", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_combine_bwd",
-    "moe_gate_topk_bwd",
+    "moe_gate_topk_bwd", "moe_permute_lite", "moe_grouped_ffn_fwd_groups",
 ]
 
 
@@ -152,6 +152,43 @@ def moe_grouped_ffn_fwd(s: Shape, x_perm, offsets, w1, w3, w2, y_perm, a_save, b
                                      _ptr(a_save, s.dtype, (s.R, s.f), "a_save"),
                                      _ptr(b_save, s.dtype, (s.R, s.f), "b_save"), wp, wn, _stream()),
            "moe_grouped_ffn_fwd")
+
+
+def moe_permute_lite(s: Shape, G: int, x, topk_ids, rep_begin, rep_group, expert_counts, group_counts, group_offsets,
+                     row_of_pair, pair_of_row, x_perm, table_errors, ws):
+    c = s.c()
+    wp, wn = _ws(ws)
+    n_rep = int(rep_group.numel())
+    _check(lib().moe_permute_lite(ctypes.byref(c), ctypes.c_int32(G), ctypes.c_int32(n_rep),
+                                  _ptr(x, s.dtype, (s.T, s.d), "x"),
+                                  _ptr(topk_ids, torch.int32, (s.T, s.k), "topk_ids"),
+                                  _ptr(rep_begin, torch.int32, (s.E + 1,), "rep_begin"),
+                                  _ptr(rep_group, torch.int32, (n_rep,), "rep_group"),
+                                  _ptr(expert_counts, torch.int32, (s.E,), "expert_counts"),
+                                  _ptr(group_counts, torch.int32, (G,), "group_counts"),
+                                  _ptr(group_offsets, torch.int32, (G + 1,), "group_offsets"),
+                                  _ptr(row_of_pair, torch.int32, (s.R,), "row_of_pair"),
+                                  _ptr(pair_of_row, torch.int32, (s.R,), "pair_of_row"),
+                                  _ptr(x_perm, s.dtype, (s.R, s.d), "x_perm"),
+                                  _ptr(table_errors, torch.int32, (1,), "table_errors"), wp, wn, _stream()),
+           "moe_permute_lite")
+
+
+def moe_grouped_ffn_fwd_groups(s: Shape, G: int, expert_of_group, x_perm, group_offsets, w1, w3, w2, y_perm, a_save,
+                               b_save, ws):
+    c = s.c()
+    wp, wn = _ws(ws)
+    _check(lib().moe_grouped_ffn_fwd_groups(ctypes.byref(c), ctypes.c_int32(G),
+                                            _ptr(expert_of_group, torch.int32, (G,), "expert_of_group"),
+                                            _ptr(x_perm, s.dtype, (s.R, s.d), "x_perm"),
+                                            _ptr(group_offsets, torch.int32, (G + 1,), "group_offsets"),
+                                            _ptr(w1, s.dtype, (s.E, s.d, s.f), "w1"),
+                                            _ptr(w3, s.dtype, (s.E, s.d, s.f), "w3"),
+                                            _ptr(w2, s.dtype, (s.E, s.f, s.d), "w2"),
+                                            _ptr(y_perm, s.dtype, (s.R, s.d), "y_perm"),
+                                            _ptr(a_save, s.dtype, (s.R, s.f), "a_save"),
+                                            _ptr(b_save, s.dtype, (s.R, s.f), "b_save"), wp, wn, _stream()),
+           "moe_grouped_ffn_fwd_groups")
 
 
 def moe_grouped_ffn_bwd(s: Shape, x_perm, offsets, w1, w3, w2, a_save, b_save, dy_perm, dx_perm, dw1, dw3, dw2, ws):

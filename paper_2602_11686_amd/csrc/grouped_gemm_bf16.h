@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
 #pragma unroll
         for (int sgi = 0; sgi < 2; ++sgi) {
             const int q = sgi < g.nseg ? sgi : 0;
-            const int64_t eoff = RAGK ? 0 : (int64_t)di.e * g.strideB;
+            const int64_t eoff = RAGK ? 0 : (int64_t)weight_index(g, di.e) * g.strideB;
             iA[sgi] = static_cast<const bf16_t*>(g.seg[q].A);
             iB[sgi] = static_cast<const bf16_t*>(g.seg[q].B) + eoff;
             iB2[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;

@@ -54,7 +54,16 @@ struct GArgs {
     int64_t ldc;
     const int32_t* order;  // ragged K: experts by row count, heaviest first (may be null)
     const void* zero_row;  // ragged K: 512 bytes of zeros in device memory
+    const int32_t* expert_of_group;  // ragged M: weights of group e are those of expert expert_of_group[e] (null: e itself)
+    int n_weights;                   // experts in the weight arrays (the table's entries are clamped to it)
 };
+
+// index of the weight matrices of group e
+__device__ __forceinline__ int weight_index(const GArgs& g, int e) {
+    if (!g.expert_of_group) return e;
+    const int w = g.expert_of_group[e];
+    return w < 0 ? 0 : (w >= g.n_weights ? g.n_weights - 1 : w);
+}
 
 template <class T, int EPI>
 __device__ __forceinline__ void epilogue_elem(const GArgs& g, int64_t idx, float a, float b) {
@@ -194,13 +203,13 @@ __global__ __launch_bounds__(256) void gg_bf16_kernel(const GArgs g) {
     auto gload = [&](int it) {
         const int sg = it / nk, k0 = kbeg + (it - sg * nk) * BK;
         const bf16_t* A = static_cast<const bf16_t*>(g.seg[sg].A);
-        const bf16_t* B = static_cast<const bf16_t*>(g.seg[sg].B) + (RAGK ? 0 : (int64_t)e * g.strideB);
+        const bf16_t* B = static_cast<const bf16_t*>(g.seg[sg].B) + (RAGK ? 0 : (int64_t)weight_index(g, e) * g.strideB);
         if constexpr (AT == 0) ld_kcontig(ra, A, g.lda, m0, m_lim, k0, kend);
         else ld_strided(ra, A, g.lda, k0, kend, m0, m_lim);
         if constexpr (BT == 1) ld_kcontig(rb, B, g.ldb, n0, g.N, k0, kend);
         else ld_strided(rb, B, g.ldb, k0, kend, n0, g.N);
         if constexpr (DUAL) {
-            const bf16_t* B2 = static_cast<const bf16_t*>(g.seg[sg].B2) + (RAGK ? 0 : (int64_t)e * g.strideB);
+            const bf16_t* B2 = static_cast<const bf16_t*>(g.seg[sg].B2) + (RAGK ? 0 : (int64_t)weight_index(g, e) * g.strideB);
             if constexpr (BT == 1) ld_kcontig(rb2, B2, g.ldb, n0, g.N, k0, kend);
             else ld_strided(rb2, B2, g.ldb, k0, kend, n0, g.N);
         }
@@ -293,8 +302,8 @@ __global__ __launch_bounds__(256) void gg_f32_kernel(const GArgs g, const F32Str
 
     for (int sg = 0; sg < g.nseg; ++sg) {
         const float* A = static_cast<const float*>(g.seg[sg].A);
-        const float* B = static_cast<const float*>(g.seg[sg].B) + (RAGK ? 0 : (int64_t)e * g.strideB);
-        const float* B2 = DUAL ? static_cast<const float*>(g.seg[sg].B2) + (RAGK ? 0 : (int64_t)e * g.strideB) : nullptr;
+        const float* B = static_cast<const float*>(g.seg[sg].B) + (RAGK ? 0 : (int64_t)weight_index(g, e) * g.strideB);
+        const float* B2 = DUAL ? static_cast<const float*>(g.seg[sg].B2) + (RAGK ? 0 : (int64_t)weight_index(g, e) * g.strideB) : nullptr;
         for (int k0 = kbeg; k0 < kend; k0 += TK) {
             __syncthreads();
             for (int idx = threadIdx.x; idx < TK * TM; idx += 256) {
@@ -415,20 +424,24 @@ size_t ffn_bwd_workspace_bytes(const moe_shape* s) {
 
 using namespace moe;
 
+// groups: number of row groups described by offsets (the experts themselves, or replica groups whose weights
+// are those of expert expert_of_group[g])
 static void run_fwd1(const moe_shape* s, const void* x_perm, const int32_t* offsets, const void* w1, const void* w3,
-                     void* H, void* a_save, void* b_save, hipStream_t st) {
+                     void* H, void* a_save, void* b_save, hipStream_t st, int groups = 0,
+                     const int32_t* expert_of_group = nullptr) {
     GArgs g{};
-    g.offsets = offsets; g.E = s->E; g.N = s->f; g.K = s->d; g.nseg = 1;
+    g.offsets = offsets; g.E = groups ? groups : s->E; g.N = s->f; g.K = s->d; g.nseg = 1;
+    g.expert_of_group = expert_of_group; g.n_weights = s->E;
     g.seg[0] = {x_perm, w1, w3};
     g.lda = s->d; g.ldb = s->f; g.strideB = (int64_t)s->d * s->f;
     g.C0 = H; g.S0 = a_save; g.S1 = b_save; g.ldc = s->f;
     launch_gg<0, 0, true, EPI_SWIGLU, false>(s, g, (int64_t)s->T * s->k, st);
 }
 
-extern "C" moe_status moe_grouped_ffn_fwd(const moe_shape* s, const void* x_perm, const int32_t* offsets,
-                                          const void* w1, const void* w3, const void* w2, void* y_perm, void* a_save,
-                                          void* b_save, void* ws, size_t ws_bytes, void* stream) {
-    const char* who = "moe_grouped_ffn_fwd";
+static moe_status ffn_fwd_impl(const char* who, const moe_shape* s, int groups, const int32_t* expert_of_group,
+                               const void* x_perm, const int32_t* offsets, const void* w1, const void* w3,
+                               const void* w2, void* y_perm, void* a_save, void* b_save, void* ws, size_t ws_bytes,
+                               void* stream) {
     MOE_RETURN_IF(check_shape(s, who));
     MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who));
     MOE_RETURN_IF(check_ptr(offsets, "offsets", who));
@@ -450,14 +463,36 @@ extern "C" moe_status moe_grouped_ffn_fwd(const moe_shape* s, const void* x_perm
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t R = (int64_t)s->T * s->k;
     void* H = ws;
-    run_fwd1(s, x_perm, offsets, w1, w3, H, a_save, b_save, st);
+    run_fwd1(s, x_perm, offsets, w1, w3, H, a_save, b_save, st, groups, expert_of_group);
     GArgs g{};
-    g.offsets = offsets; g.E = s->E; g.N = s->d; g.K = s->f; g.nseg = 1;
+    g.offsets = offsets; g.E = groups; g.N = s->d; g.K = s->f; g.nseg = 1;
+    g.expert_of_group = expert_of_group; g.n_weights = s->E;
     g.seg[0] = {H, w2, nullptr};
     g.lda = s->f; g.ldb = s->d; g.strideB = (int64_t)s->f * s->d;
     g.C0 = y_perm; g.ldc = s->d;
     launch_gg<0, 0, false, EPI_STORE, false>(s, g, R, st);
     return launch_status(who);
+}
+
+extern "C" moe_status moe_grouped_ffn_fwd(const moe_shape* s, const void* x_perm, const int32_t* offsets,
+                                          const void* w1, const void* w3, const void* w2, void* y_perm, void* a_save,
+                                          void* b_save, void* ws, size_t ws_bytes, void* stream) {
+    return ffn_fwd_impl("moe_grouped_ffn_fwd", s, s ? s->E : 0, nullptr, x_perm, offsets, w1, w3, w2, y_perm, a_save,
+                        b_save, ws, ws_bytes, stream);
+}
+
+extern "C" moe_status moe_grouped_ffn_fwd_groups(const moe_shape* s, int32_t G, const int32_t* expert_of_group,
+                                                 const void* x_perm, const int32_t* group_offsets, const void* w1,
+                                                 const void* w3, const void* w2, void* y_perm, void* a_save,
+                                                 void* b_save, void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "moe_grouped_ffn_fwd_groups";
+    if (G < 1 || G > MOE_MAX_EXPERTS) {
+        set_error("%s: G=%d must be in [1, %d]", who, G, MOE_MAX_EXPERTS);
+        return MOE_ERR_INVALID_ARG;
+    }
+    MOE_RETURN_IF(check_ptr(expert_of_group, "expert_of_group", who));
+    return ffn_fwd_impl(who, s, G, expert_of_group, x_perm, group_offsets, w1, w3, w2, y_perm, a_save, b_save, ws,
+                        ws_bytes, stream);
 }
 
 extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm, const int32_t* offsets,

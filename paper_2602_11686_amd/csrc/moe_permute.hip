@@ -23,11 +23,14 @@ namespace moe {
 constexpr int kChunk = 512;        // pairs per wavefront in the sort
 constexpr int kWavesPerBlock = 4;  // 256 threads
 
+constexpr size_t kLiteTableBytes = (4 * MOE_MAX_EXPERTS + 64) * sizeof(int32_t);
+
 static inline int num_chunks(int64_t R) { return (int)((R + kChunk - 1) / kChunk); }
 
 size_t permute_workspace_bytes(const moe_shape* s) {
     const int64_t R = (int64_t)s->T * s->k;
-    return 2 * align_up((size_t)num_chunks(R) * s->E * sizeof(int32_t), 256);  // chunk histograms + chunk bases
+    // chunk histograms + chunk bases + (lite routing) four per-expert tables and a flag
+    return 2 * align_up((size_t)num_chunks(R) * s->E * sizeof(int32_t), 256) + kLiteTableBytes;
 }
 
 // ---- 1. per-chunk histogram ---------------------------------------------------
@@ -137,6 +140,169 @@ __global__ __launch_bounds__(256) void permute_rank_kernel(const int32_t* __rest
         }
         // the highest lane of each group advances the expert's counter; the wave
         // executes in lockstep, so all reads above precede these writes
+        __builtin_amdgcn_wave_barrier();
+        if (live && (same >> lane) == 1ull) next[e] += __popcll(same);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---- 2L / 3L. the same sort with the lite routing of the paper's appendix folded in ---------------
+// Every expert e has a list of replica groups rep_group[rep_begin[e] .. rep_begin[e+1]) (the replicas the
+// sending device may use: those in its node, else all).  The n_e pairs of the expert, in stable order, are
+// cut into len consecutive blocks whose sizes differ by at most one (larger blocks first); block r goes to
+// group rep_group[rep_begin[e] + r].  Rows are ordered by group.
+//
+// The table comes from outside and is checked here: list bounds, a list for every expert that has pairs,
+// group ids inside [0, G), no group listed twice.  If a check fails, *table_errors is set and the rows fall
+// back to plain expert order with all of them counted in group 0, so that every index written stays inside
+// [0, R) whatever the table holds.
+struct LiteTables {          // in the workspace, written by the scan, read by the rank kernel
+    int32_t* lo;             // [E] first list entry of the expert        (fallback: first row of the expert)
+    int32_t* base;           // [E] n_e / len
+    int32_t* rem;            // [E] n_e % len
+    int32_t* ok;             // [1]
+};
+
+__global__ __launch_bounds__(256) void permute_scan_lite_kernel(const int32_t* __restrict__ chunk_hist,
+                                                                int32_t* __restrict__ chunk_base, int nchunks, int E,
+                                                                int G, int n_rep, int R,
+                                                                const int32_t* __restrict__ rep_begin,
+                                                                const int32_t* __restrict__ rep_group,
+                                                                int32_t* __restrict__ expert_counts,
+                                                                int32_t* __restrict__ group_counts,
+                                                                int32_t* __restrict__ group_offsets, LiteTables tb,
+                                                                int32_t* __restrict__ table_errors) {
+    __shared__ int32_t cnt[MOE_MAX_EXPERTS];
+    __shared__ int32_t off[MOE_MAX_EXPERTS + 1];
+    __shared__ int32_t listed[MOE_MAX_EXPERTS];
+    __shared__ int32_t gcnt[MOE_MAX_EXPERTS];
+    __shared__ int32_t bad;
+    const int e = threadIdx.x;
+    int32_t n = 0;
+    if (e < E) {
+        for (int c = 0; c < nchunks; ++c) n += chunk_hist[(size_t)c * E + e];
+        cnt[e] = n;
+        expert_counts[e] = n;
+    }
+    listed[e] = 0;
+    gcnt[e] = 0;
+    if (e == 0) bad = 0;
+    __syncthreads();
+    int lo = 0, hi = 0;
+    if (e < E) {
+        lo = rep_begin[e];
+        hi = rep_begin[e + 1];
+        if (lo < 0 || hi < lo || hi > n_rep) {
+            atomicOr(&bad, 1);
+            lo = hi = 0;
+        } else {
+            if (n > 0 && hi == lo) atomicOr(&bad, 2);
+            for (int r = lo; r < hi; ++r) {
+                const int g = rep_group[r];
+                if ((unsigned)g >= (unsigned)G) atomicOr(&bad, 4);
+                else if (atomicAdd(&listed[g], 1) > 0) atomicOr(&bad, 8);
+            }
+        }
+    }
+    __syncthreads();
+    const bool ok = bad == 0;
+    if (e == 0) {  // exclusive scan of the expert counts (the fallback order)
+        int32_t run = 0;
+        for (int i = 0; i < E; ++i) {
+            off[i] = run;
+            run += cnt[i];
+        }
+        off[E] = run;
+        tb.ok[0] = ok ? 1 : 0;
+        if (table_errors) table_errors[0] = bad;
+        if (!ok) gcnt[0] = R;
+    }
+    if (e < E && ok) {
+        const int len = hi - lo;
+        const int b = len ? n / len : 0, rm = len ? n % len : 0;
+        for (int r = 0; r < len; ++r) gcnt[rep_group[lo + r]] = b + (r < rm ? 1 : 0);
+        tb.lo[e] = lo;
+        tb.base[e] = b;
+        tb.rem[e] = rm;
+    }
+    __syncthreads();
+    if (e < E && !ok) {
+        tb.lo[e] = off[e];
+        tb.base[e] = 0;
+        tb.rem[e] = 0;
+    }
+    if (e == 0) {
+        int32_t run = 0;
+        for (int g = 0; g < G; ++g) {
+            group_counts[g] = gcnt[g];
+            group_offsets[g] = run;
+            run += gcnt[g];
+        }
+        group_offsets[G] = run;
+    }
+    if (e < E) {  // rank of the first pair of every chunk inside its expert
+        int32_t run = 0;
+        for (int c = 0; c < nchunks; ++c) {
+            chunk_base[(size_t)c * E + e] = run;
+            run += chunk_hist[(size_t)c * E + e];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void permute_rank_lite_kernel(const int32_t* __restrict__ ids, int R, int E,
+                                                                const int32_t* __restrict__ chunk_base,
+                                                                const int32_t* __restrict__ rep_group,
+                                                                const int32_t* __restrict__ group_offsets,
+                                                                LiteTables tb, int32_t* __restrict__ row_of_pair,
+                                                                int32_t* __restrict__ pair_of_row) {
+    extern __shared__ int32_t lds_next[];  // [kWavesPerBlock][4][E]: next rank, list start, base, rem
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * kWavesPerBlock + wave;
+    const int p0 = chunk * kChunk;
+    if (p0 >= R) return;  // whole wavefront leaves together; no barrier below
+    int32_t* next = lds_next + wave * 4 * E;
+    int32_t* lo = next + E;
+    int32_t* base = lo + E;
+    int32_t* rem = base + E;
+    for (int e = lane; e < E; e += 64) {
+        next[e] = chunk_base[(size_t)chunk * E + e];
+        lo[e] = tb.lo[e];
+        base[e] = tb.base[e];
+        rem[e] = tb.rem[e];
+    }
+    const bool ok = tb.ok[0] != 0;
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    for (int i = 0; i < kChunk; i += 64) {
+        const int p = p0 + i + lane;
+        const bool live = p < R;
+        const int e = live ? ids[p] : -1;
+        uint64_t same = __ballot(live);
+        if (!live) same = 0;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t bal = __ballot((e >> b) & 1);
+            same &= ((e >> b) & 1) ? bal : ~bal;
+        }
+        if (live) {
+            const int q = next[e] + __popcll(same & lt_mask);  // stable rank inside the expert
+            int row;
+            if (ok) {
+                const int b = base[e], rm = rem[e], big = rm * (b + 1);
+                int r, start;
+                if (q < big) {
+                    r = q / (b + 1);
+                    start = r * (b + 1);
+                } else {  // b >= 1 here: q >= big = rm*(b+1) with b == 0 would mean q >= n_e
+                    r = rm + (q - big) / b;
+                    start = big + (r - rm) * b;
+                }
+                row = group_offsets[rep_group[lo[e] + r]] + (q - start);
+            } else {
+                row = lo[e] + q;
+            }
+            row_of_pair[p] = row;
+            pair_of_row[row] = p;
+        }
         __builtin_amdgcn_wave_barrier();
         if (live && (same >> lane) == 1ull) next[e] += __popcll(same);
         __builtin_amdgcn_wave_barrier();
@@ -291,6 +457,56 @@ extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32
     permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_hist);
     permute_scan_kernel<<<1, 256, 0, st>>>(chunk_hist, chunk_base, nchunks, E, counts, offsets);
     permute_rank_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_base, row_of_pair, pair_of_row);
+    if (x_perm) {
+        const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
+        const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);
+        permute_scatter_rows_kernel<<<grid, 256, 0, st>>>(static_cast<const u32x4*>(x), row_of_pair,
+                                                          static_cast<u32x4*>(x_perm), s->T, s->k, vecs_per_row);
+    }
+    return launch_status(who);
+}
+
+extern "C" moe_status moe_permute_lite(const moe_shape* s, int32_t G, int32_t n_rep, const void* x,
+                                       const int32_t* topk_ids, const int32_t* rep_begin, const int32_t* rep_group,
+                                       int32_t* expert_counts, int32_t* group_counts, int32_t* group_offsets,
+                                       int32_t* row_of_pair, int32_t* pair_of_row, void* x_perm,
+                                       int32_t* table_errors, void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "moe_permute_lite";
+    MOE_RETURN_IF(check_shape(s, who));
+    if (G < 1 || G > MOE_MAX_EXPERTS || n_rep < 0) {
+        set_error("%s: G=%d must be in [1, %d] and n_rep=%d >= 0", who, G, MOE_MAX_EXPERTS, n_rep);
+        return MOE_ERR_INVALID_ARG;
+    }
+    MOE_RETURN_IF(check_ptr(topk_ids, "topk_ids", who));
+    MOE_RETURN_IF(check_ptr(rep_begin, "rep_begin", who));
+    if (n_rep > 0) MOE_RETURN_IF(check_ptr(rep_group, "rep_group", who));
+    MOE_RETURN_IF(check_ptr(expert_counts, "expert_counts", who));
+    MOE_RETURN_IF(check_ptr(group_counts, "group_counts", who));
+    MOE_RETURN_IF(check_ptr(group_offsets, "group_offsets", who));
+    MOE_RETURN_IF(check_ptr(row_of_pair, "row_of_pair", who));
+    MOE_RETURN_IF(check_ptr(pair_of_row, "pair_of_row", who));
+    MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who, true));
+    if (x_perm) MOE_RETURN_IF(check_ptr(x, "x", who));
+    MOE_RETURN_IF(check_ptr(table_errors, "table_errors", who, true));
+    MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    if (ws_bytes < permute_workspace_bytes(s)) {
+        set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, permute_workspace_bytes(s));
+        return MOE_ERR_WORKSPACE_TOO_SMALL;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int R = s->T * s->k, E = s->E;
+    const int nchunks = num_chunks(R);
+    const int nblocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
+    const size_t hist_ints = align_up((size_t)nchunks * E * sizeof(int32_t), 256) / sizeof(int32_t);
+    int32_t* chunk_hist = static_cast<int32_t*>(ws);
+    int32_t* chunk_base = chunk_hist + hist_ints;
+    int32_t* tables = chunk_base + hist_ints;
+    LiteTables tb{tables, tables + MOE_MAX_EXPERTS, tables + 2 * MOE_MAX_EXPERTS, tables + 4 * MOE_MAX_EXPERTS};
+    permute_hist_kernel<<<nblocks, 256, (size_t)kWavesPerBlock * E * sizeof(int32_t), st>>>(topk_ids, R, E, chunk_hist);
+    permute_scan_lite_kernel<<<1, 256, 0, st>>>(chunk_hist, chunk_base, nchunks, E, G, n_rep, R, rep_begin, rep_group,
+                                                expert_counts, group_counts, group_offsets, tb, table_errors);
+    permute_rank_lite_kernel<<<nblocks, 256, (size_t)kWavesPerBlock * 4 * E * sizeof(int32_t), st>>>(
+        topk_ids, R, E, chunk_base, rep_group, group_offsets, tb, row_of_pair, pair_of_row);
     if (x_perm) {
         const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
         const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);

@@ -370,3 +370,57 @@ extern "C" moe_status moe_plan_expert_layout(const moe_plan_shape* s, const moe_
     *best_index = best_i;
     return MOE_OK;
 }
+
+extern "C" moe_status moe_plan_dispatch_table(const moe_plan_shape* s, const int32_t* A, int32_t rank, int32_t* G_out,
+                                              int32_t* n_rep_out, int32_t* expert_of_group, int32_t* device_of_group,
+                                              int32_t* rep_begin, int32_t* rep_group) {
+    const char* who = "moe_plan_dispatch_table";
+    MOE_RETURN_IF(check_shape(s, who));
+    PLAN_NOT_NULL(A, who);
+    PLAN_NOT_NULL(G_out, who);
+    PLAN_NOT_NULL(n_rep_out, who);
+    PLAN_NOT_NULL(expert_of_group, who);
+    PLAN_NOT_NULL(device_of_group, who);
+    PLAN_NOT_NULL(rep_begin, who);
+    PLAN_NOT_NULL(rep_group, who);
+    const int N = s->N, E = s->E, D = s->D;
+    if (rank < 0 || rank >= N) {
+        set_error("%s: rank %d outside [0, %d)", who, rank, N);
+        return MOE_ERR_INVALID_ARG;
+    }
+    int64_t total = 0;
+    for (int64_t q = 0; q < (int64_t)N * E; ++q) {
+        if (A[q] < 0) {
+            set_error("%s: A has a negative entry", who);
+            return MOE_ERR_INVALID_ARG;
+        }
+        total += A[q];
+    }
+    if (total > (int64_t)N * s->C) {
+        set_error("%s: the layout holds %lld replicas, more than N*C = %lld", who, (long long)total, (long long)N * s->C);
+        return MOE_ERR_INVALID_ARG;
+    }
+    int G = 0;
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < E; ++j)
+            for (int m = 0; m < A[(size_t)i * E + j]; ++m) {
+                expert_of_group[G] = j;
+                device_of_group[G] = i;
+                ++G;
+            }
+    const int node = rank / D;
+    int n = 0;
+    rep_begin[0] = 0;
+    for (int j = 0; j < E; ++j) {
+        const int first = n;
+        for (int g = 0; g < G; ++g)
+            if (expert_of_group[g] == j && device_of_group[g] / D == node) rep_group[n++] = g;
+        if (n == first)
+            for (int g = 0; g < G; ++g)
+                if (expert_of_group[g] == j) rep_group[n++] = g;
+        rep_begin[j + 1] = n;
+    }
+    *G_out = G;
+    *n_rep_out = n;
+    return MOE_OK;
+}

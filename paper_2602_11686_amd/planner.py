@@ -14,7 +14,7 @@ import numpy as np
 from .binding import MoeError, lib
 
 PLANNER_EXPORTS = ["moe_plan_replica_allocation", "moe_plan_expert_relocation", "moe_plan_lite_routing",
-                   "moe_plan_time_cost", "moe_plan_expert_layout"]
+                   "moe_plan_time_cost", "moe_plan_expert_layout", "moe_plan_dispatch_table"]
 
 
 class _CPlanShape(ctypes.Structure):
@@ -115,3 +115,16 @@ def moe_plan_expert_layout(s: PlanShape, c: PlanCost, R, eps: int, seed: int, wa
     if want_candidates:
         return A, T.value, best.value, cands
     return A, T.value, best.value
+
+
+def moe_plan_dispatch_table(s: PlanShape, A, rank: int):
+    """Returns (G, expert_of_group[G], device_of_group[G], rep_begin[E+1], rep_group[n_rep]) as numpy int32."""
+    A = _arr(A, np.int32, (s.N, s.E), "A")
+    cap = s.N * s.C
+    eog, dog = np.empty(cap, np.int32), np.empty(cap, np.int32)
+    rb, rg = np.empty(s.E + 1, np.int32), np.empty(cap, np.int32)
+    G, n_rep = ctypes.c_int32(0), ctypes.c_int32(0)
+    cs = s.c()
+    _check(lib().moe_plan_dispatch_table(ctypes.byref(cs), _p(A), ctypes.c_int32(rank), ctypes.byref(G),
+                                         ctypes.byref(n_rep), _p(eog), _p(dog), _p(rb), _p(rg)), "moe_plan_dispatch_table")
+    return G.value, eog[:G.value].copy(), dog[:G.value].copy(), rb, rg[:n_rep.value].copy()

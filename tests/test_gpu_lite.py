@@ -1,0 +1,171 @@
+"""GPU parity of the token dispatcher (moe_permute_lite, moe_grouped_ffn_fwd_groups) through the C ABI:
+integer outputs bit-exact against oracle/lite_oracle.py; the layer output over replica groups bit-identical
+to the plain path (replicas share weights) and within the bf16 bar of the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lite_oracle as DO
+from oracle import oracle as O
+from oracle import planner_oracle as PO
+from paper_2602_11686_amd import binding as B
+from paper_2602_11686_amd import inputs as I
+from tests.gpu_common import TOL, host
+from tests.helpers import rel_max
+
+pytestmark = pytest.mark.gpu
+
+
+def i32(a):
+    return torch.tensor(np.asarray(a, dtype=np.int32), dtype=torch.int32, device="cuda")
+
+
+def layout_for(ids, E, N, C, Dn, rank, seed):
+    """A layout from the planner oracle for a cluster in which `rank` holds these ids and the other devices
+    hold seeded random loads of the same skew."""
+    rng = np.random.default_rng(seed)
+    mine = np.bincount(ids.reshape(-1), minlength=E)
+    R = rng.poisson(np.maximum(mine, 1)[None, :] * rng.uniform(0.5, 1.5, size=(N, 1))).astype(np.int64)
+    R[rank] = mine
+    A = PO.expert_relocation(PO.replica_allocation(R.tolist(), N, E, C), R.sum(axis=0).tolist(), N, E, C, Dn)
+    return DO.dispatch_table(A, N, E, Dn, rank)
+
+
+def random_ids(seed, T, E, k, skew=1.5):
+    rng = np.random.default_rng(seed)
+    w = 1.0 / np.arange(1, E + 1) ** skew
+    w = w[rng.permutation(E)]
+    g = rng.gumbel(size=(T, E)) + np.log(w)[None, :]
+    return np.argsort(-g, axis=1)[:, :k].astype(np.int32)
+
+
+def run_permute_lite(s, G, x, ids, rb, rg):
+    ec = torch.empty(s.E, dtype=torch.int32, device="cuda")
+    gc = torch.empty(G, dtype=torch.int32, device="cuda")
+    go = torch.empty(G + 1, dtype=torch.int32, device="cuda")
+    rop = torch.empty(s.R, dtype=torch.int32, device="cuda")
+    por = torch.empty(s.R, dtype=torch.int32, device="cuda")
+    xp = torch.empty(s.R, s.d, dtype=s.dtype, device="cuda") if x is not None else None
+    err = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    B.moe_permute_lite(s, G, x, i32(ids), i32(rb), i32(rg), ec, gc, go, rop, por, xp, err, ws)
+    torch.cuda.synchronize()
+    return ec, gc, go, rop, por, xp, err
+
+
+CASES = [  # T, E, k, N, C, D, rank
+    (1, 4, 2, 4, 2, 2, 1),
+    (300, 8, 2, 8, 2, 4, 5),
+    (1000, 8, 2, 32, 2, 8, 9),
+    (777, 64, 4, 32, 4, 8, 31),
+    (2048, 130, 3, 64, 4, 8, 17),
+    (513, 16, 16, 16, 2, 8, 0),
+    (4096, 128, 8, 32, 8, 8, 12),
+    (8192, 64, 4, 32, 4, 8, 5),      # cfg2's routing shape on a 32-device cluster, G = 128
+    (16384, 8, 2, 32, 2, 8, 20),     # cfg3's (Mixtral e8k2, the paper's cluster: 4 nodes of 8, C = 2), G = 64
+]
+
+
+@pytest.mark.parametrize("T,E,k,N,C,Dn,rank", CASES)
+def test_permute_lite_matches_the_oracle(T, E, k, N, C, Dn, rank):
+    print(f"case T={T} E={E} k={k} N={N} C={C} D={Dn} rank={rank}", flush=True)
+    ids = random_ids(T + E, T, E, k)
+    G, eog, dog, rb, rg = layout_for(ids, E, N, C, Dn, rank, seed=T)
+    assert G <= 256
+    d = 64
+    s = B.Shape(T, d, 64, E, k, torch.bfloat16)
+    x = torch.randn(T, d, device="cuda").bfloat16()
+    ec, gc, go, rop, por, xp, err = run_permute_lite(s, G, x, ids, rb, rg)
+    r_ec, r_gc, r_go, r_rop, r_por = DO.permute_lite(ids.tolist(), E, G, rb, rg)
+    assert int(err[0]) == 0
+    assert host(ec).tolist() == r_ec and host(gc).tolist() == r_gc and host(go).tolist() == r_go
+    assert host(rop).tolist() == r_rop and host(por).tolist() == r_por
+    src = torch.tensor(np.asarray(r_por) // k, device="cuda")
+    assert torch.equal(xp.view(torch.int16), x[src].view(torch.int16))          # rows are bitwise copies
+
+
+def test_without_replication_equals_moe_permute():
+    T, E, k, d = 2000, 32, 4, 128
+    ids = random_ids(5, T, E, k)
+    s = B.Shape(T, d, 64, E, k, torch.bfloat16)
+    x = torch.randn(T, d, device="cuda").bfloat16()
+    ec, gc, go, rop, por, xp, err = run_permute_lite(s, E, x, ids, list(range(E + 1)), list(range(E)))
+    counts = torch.empty(E, dtype=torch.int32, device="cuda"); offsets = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    rop2 = torch.empty_like(rop); por2 = torch.empty_like(por); xp2 = torch.empty_like(xp)
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    B.moe_permute(s, x, i32(ids), counts, offsets, rop2, por2, xp2, ws)
+    torch.cuda.synchronize()
+    assert int(err[0]) == 0 and torch.equal(gc, counts) and torch.equal(go, offsets) and torch.equal(ec, counts)
+    assert torch.equal(rop, rop2) and torch.equal(por, por2) and torch.equal(xp.view(torch.int16), xp2.view(torch.int16))
+
+
+@pytest.mark.parametrize("what", ["no_list", "group_out_of_range", "group_twice", "list_out_of_bounds", "decreasing"])
+def test_a_bad_table_is_reported_and_stays_in_bounds(what):
+    T, E, k, G = 500, 8, 2, 12
+    ids = random_ids(11, T, E, k, skew=0.5)            # every expert has pairs
+    rb = list(range(E + 1)); rg = list(range(E))
+    if what == "no_list":
+        rb = [0, 0] + list(range(1, E)); rg = list(range(E - 1))        # expert 0 has pairs but no replica
+    elif what == "group_out_of_range":
+        rg[3] = G
+    elif what == "group_twice":
+        rg[5] = rg[2]
+    elif what == "list_out_of_bounds":
+        rb[E] = E + 3
+    elif what == "decreasing":
+        rb[4] = 2
+    s = B.Shape(T, 64, 64, E, k, torch.bfloat16)
+    ec, gc, go, rop, por, xp, err = run_permute_lite(s, G, None, ids, rb, rg)
+    assert int(err[0]) != 0
+    counts = np.bincount(ids.reshape(-1), minlength=E)
+    assert host(ec).tolist() == counts.tolist()
+    assert host(gc).tolist() == [T * k] + [0] * (G - 1) and host(go).tolist() == [0] + [T * k] * G
+    x = np.zeros((T, 4), np.float32)
+    _, _, r_rop, r_por, _ = O.permute(x, ids, E)  # plain expert order
+    assert host(rop).tolist() == r_rop.tolist() and host(por).tolist() == r_por.tolist()
+
+
+@pytest.mark.parametrize("T,d,f,E,k,N,C,Dn,rank", [(600, 256, 384, 8, 2, 8, 2, 4, 3), (1500, 512, 256, 16, 4, 16, 4, 8, 9)])
+def test_layer_over_replica_groups(T, d, f, E, k, N, C, Dn, rank):
+    """permute_lite -> grouped FFN over groups -> combine gives the bits of permute -> grouped FFN -> combine,
+    and both sit within the bf16 bar of the oracle's layer."""
+    print(f"case T={T} d={d} f={f} E={E} k={k}", flush=True)
+    rng = np.random.default_rng(T)
+    bits = lambda a: I.f32_to_bf16_bits(a.astype(np.float32))
+    xb = bits(rng.standard_normal((T, d))); w1b = bits(rng.standard_normal((E, d, f)) * 0.05)
+    w3b = bits(rng.standard_normal((E, d, f)) * 0.05); w2b = bits(rng.standard_normal((E, f, d)) * 0.05)
+    ids = random_ids(T, T, E, k)
+    wts = rng.random((T, k)).astype(np.float32); wts /= wts.sum(1, keepdims=True)
+    G, eog, dog, rb, rg = layout_for(ids, E, N, C, Dn, rank, seed=1)
+    to = lambda b: torch.tensor(b.view(np.int16), device="cuda").view(torch.bfloat16)
+    x, w1, w3, w2 = to(xb), to(w1b), to(w3b), to(w2b)
+    s = B.Shape(T, d, f, E, k, torch.bfloat16)
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    tw = torch.tensor(wts, device="cuda")
+    # plain path
+    counts = torch.empty(E, dtype=torch.int32, device="cuda"); offsets = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    rop = torch.empty(s.R, dtype=torch.int32, device="cuda"); por = torch.empty_like(rop)
+    xp = torch.empty(s.R, d, dtype=torch.bfloat16, device="cuda"); yp = torch.empty_like(xp); y = torch.empty_like(x)
+    B.moe_permute(s, x, i32(ids), counts, offsets, rop, por, xp, ws)
+    B.moe_grouped_ffn_fwd(s, xp, offsets, w1, w3, w2, yp, None, None, ws)
+    B.moe_unpermute_combine(s, yp, rop, tw, y)
+    # lite path
+    ec, gc, go, rop_l, por_l, xp_l, err = run_permute_lite(s, G, x, ids, rb, rg)
+    yp_l = torch.empty_like(xp); y_l = torch.empty_like(x)
+    B.moe_grouped_ffn_fwd_groups(s, G, i32(eog), xp_l, go, w1, w3, w2, yp_l, None, None, ws)
+    B.moe_unpermute_combine(s, yp_l, rop_l, tw, y_l)
+    torch.cuda.synchronize()
+    assert int(err[0]) == 0
+    assert torch.equal(y.view(torch.int16), y_l.view(torch.int16))
+    assert torch.equal(yp[rop.long()].view(torch.int16), yp_l[rop_l.long()].view(torch.int16))
+    # oracle: grouped FFN over the groups with the weights gathered per group, then the combine
+    f64 = lambda b: I.bf16_bits_to_f32(b).astype(np.float64)
+    r = DO.permute_lite(ids.tolist(), E, G, rb, rg)
+    go_ref, rop_ref, por_ref = np.asarray(r[2], np.int32), np.asarray(r[3], np.int32), np.asarray(r[4], np.int32)
+    X = f64(xb)
+    Xp = X[por_ref // k]
+    e = np.asarray(eog)
+    Yp = O.ffn_fwd(Xp, go_ref, f64(w1b)[e], f64(w3b)[e], f64(w2b)[e])[0]
+    Y = O.unpermute_combine(Yp, rop_ref, wts.astype(np.float64), T)
+    assert rel_max(host(yp_l), Yp) <= TOL[torch.bfloat16]
+    assert rel_max(host(y_l), Y) <= TOL[torch.bfloat16]

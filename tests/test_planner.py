@@ -115,3 +115,15 @@ def test_large_cluster_solves_quickly():
     print(f"expert layout N={N} E={E} C={C}: {dt*1e3:.1f} ms")
     assert (A.sum(axis=1) == C).all() and (A.sum(axis=0) >= 1).all() and A.sum() == N * C
     assert dt < 30.0
+
+
+@pytest.mark.parametrize("seed,N,E,C,D", cases()[::2])
+def test_dispatch_table_matches_the_oracle(seed, N, E, C, D):
+    from oracle import lite_oracle as DO
+    s = L.PlanShape(N, E, C, D)
+    R = make_R(seed, N, E)
+    A, _, _ = L.moe_plan_expert_layout(s, L.PlanCost(**COST), R, 3, seed)
+    for rank in {0, N // 2, N - 1}:
+        G, eog, dog, rb, rg = L.moe_plan_dispatch_table(s, A, rank)
+        G_ref, eog_ref, dog_ref, rb_ref, rg_ref = DO.dispatch_table(A.tolist(), N, E, D, rank)
+        assert (G, eog.tolist(), dog.tolist(), rb.tolist(), rg.tolist()) == (G_ref, eog_ref, dog_ref, rb_ref, rg_ref)
