@@ -58,6 +58,64 @@ def cpu_baseline(w, inp, target_seconds=15.0):
                       f"{'fwd+bwd' if w.backward else 'fwd'}, fp32 oracle, {reps} pass(es), {total:.1f} s"}
 
 
+def dispatcher_leg(w, s, g, buf, counts, N=32, D=8):
+    """The planner and the token dispatcher on this workload's routing, for a synthetic cluster of N devices
+    in nodes of D (the paper's testbed: 4 nodes of 8): layout search on the host (C++), then the permutation
+    with the lite routing folded in and the grouped FFN over replica groups, timed like the other stages."""
+    import numpy as np
+    import torch
+    from paper_2602_11686_amd import binding as B
+    from paper_2602_11686_amd import planner as P
+    C = max(-(-w.E // N), min(2 if w.E <= 16 else 8, 256 // N))
+    while N * C > 256:
+        C -= 1
+    ps = P.PlanShape(N, w.E, C, D)
+    rng = np.random.default_rng(w.seed)
+    Rm = rng.poisson(np.maximum(counts, 1)[None, :] * rng.uniform(0.7, 1.3, size=(N, 1))).astype(np.int64)
+    Rm[0] = counts
+    # cost model constants: tokens of d bf16 values over 64 GB/s links inside a node, 25 GB/s between nodes,
+    # 6 d f FLOPs per token at 1 PFLOP/s
+    cost = P.PlanCost(v_comm=2.0 * w.d, b_intra=64e9, b_inter=25e9, v_comp=6.0 * w.d * w.f, b_comp=1e15, f_ckpt=0)
+    t0 = time.perf_counter()
+    A, T_model, best = P.moe_plan_expert_layout(ps, cost, Rm, 2, w.seed)
+    planner_ms = (time.perf_counter() - t0) * 1e3
+    received = P.moe_plan_lite_routing(ps, Rm, A).sum(axis=(0, 1))
+    static = np.zeros((N, w.E), np.int32)
+    static[np.arange(w.E) % N, np.arange(w.E)] = 1
+    received_static = P.moe_plan_lite_routing(ps, Rm, static).sum(axis=(0, 1))
+    G, eog, dog, rb, rg = P.moe_plan_dispatch_table(ps, A, 0)
+    dev = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")
+    eog_d, rb_d, rg_d = dev(eog), dev(rb), dev(rg)
+    ec = torch.empty(w.E, dtype=torch.int32, device="cuda")
+    gc = torch.empty(G, dtype=torch.int32, device="cuda")
+    go = torch.empty(G + 1, dtype=torch.int32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, n):
+        for _ in range(3):
+            fn()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    perm = lambda: B.moe_permute_lite(s, G, g["x"], buf.topk_ids, rb_d, rg_d, ec, gc, go, buf.row_of_pair,
+                                      buf.pair_of_row, buf.x_perm, err, buf.ws)
+    ffn = lambda: B.moe_grouped_ffn_fwd_groups(s, G, eog_d, buf.x_perm, go, g["w1"], g["w3"], g["w2"], buf.y_perm,
+                                               None, None, buf.ws)
+    perm_ms = timed(perm, 20)
+    ffn_ms = timed(ffn, 5)
+    return {"cluster": {"N": N, "D": D, "C": C, "G": G}, "planner_layout_ms": round(planner_ms, 3),
+            "modelled_T_s": T_model, "device_load_max_over_mean": {"static_ep": float(received_static.max() / received_static.mean()),
+                                                                    "after_relayout": float(received.max() / received.mean())},
+            "permute_lite_ms": round(perm_ms, 4), "ffn_fwd_groups_ms": round(ffn_ms, 4),
+            "table_errors": int(err.item())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -178,6 +236,7 @@ def main():
                      "flops_per_launch": flops, "ms_per_launch": ffn_ms},
         "stages": stages,
     }
+    out["dispatcher"] = dispatcher_leg(w, s, g, buf, counts)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))

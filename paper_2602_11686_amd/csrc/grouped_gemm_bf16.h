@@ -172,6 +172,8 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             if (e <= g.E) t_pref[e] = run;
             run += c[u];
         }
+        // E == MOE_MAX_EXPERTS: the total belongs to "lane 64"; the last lane holds it after its four experts
+        if (lane == 63) t_pref[MOE_MAX_EXPERTS] = run;
     }
     __syncthreads();
     const int total_tiles = t_pref[g.E];

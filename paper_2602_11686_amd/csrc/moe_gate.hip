@@ -405,10 +405,14 @@ static inline int dwg_chunks(int Tn) { return (Tn + kDwgTokens - 1) / kDwgTokens
 
 // ---- bf16: dW_g through the grouped GEMM --------------------------------------------------
 // dL is written out densely as two bf16 matrices hi + lo (the pair carries 16 mantissa bits
-// of the fp32 value), tokens are cut into chunks of kMmaChunk, each chunk's X^T * dL is one
+// of the fp32 value), tokens are cut into chunks, each chunk's X^T * dL is one
 // ragged-K GEMM group, and the chunk partials are added in chunk order.
-constexpr int kMmaChunk = 512;
-static inline int mma_chunks(int Tn) { return (Tn + kMmaChunk - 1) / kMmaChunk; }
+// (512 tokens, or more for very long batches: the GEMM's group table holds MOE_MAX_EXPERTS groups)
+static inline int mma_chunk_tokens(int Tn) {
+    const int need = (Tn + MOE_MAX_EXPERTS - 1) / MOE_MAX_EXPERTS;
+    return need <= 512 ? 512 : (need + 31) / 32 * 32;
+}
+static inline int mma_chunks(int Tn) { const int c = mma_chunk_tokens(Tn); return (Tn + c - 1) / c; }
 static inline int pad8(int v) { return (v + 7) / 8 * 8; }
 
 // one wavefront per token: dl[t,s] (fp32, for the dx update) and the dense hi/lo rows
@@ -432,10 +436,11 @@ __global__ __launch_bounds__(256) void gate_dl_dense_kernel(const int32_t* __res
     }
 }
 
-__global__ void gate_chunk_offsets_kernel(int32_t* __restrict__ off, int nchunks, int Tn, uint32_t* __restrict__ zero_row) {
+__global__ void gate_chunk_offsets_kernel(int32_t* __restrict__ off, int nchunks, int chunk_tokens, int Tn,
+                                          uint32_t* __restrict__ zero_row) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < 128) zero_row[i] = 0u;
-    if (i <= nchunks) off[i] = min(i * kMmaChunk, Tn);
+    if (i <= nchunks) off[i] = (int)min((int64_t)i * chunk_tokens, (int64_t)Tn);
 }
 
 // dw_gate[c][e] = sum over chunks (in chunk order) of partial[chunk][c][e]
@@ -542,7 +547,7 @@ static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gat
         int32_t* coff = static_cast<int32_t*>(cv.take((size_t)(nch + 1) * 4));
         gate_dl_dense_kernel<<<(s->T + 3) / 4, 256, 0, st>>>(ids, w, dw, dl, hi, lo, s->T, s->k, n_pad);
         uint32_t* zero_row = static_cast<uint32_t*>(cv.take(512));
-        gate_chunk_offsets_kernel<<<(nch + 256) / 256, 256, 0, st>>>(coff, nch, s->T, zero_row);
+        gate_chunk_offsets_kernel<<<(nch + 256) / 256, 256, 0, st>>>(coff, nch, mma_chunk_tokens(s->T), s->T, zero_row);
         if (dx) {
             gate_transpose_kernel<T><<<256, 256, 0, st>>>(w_gate, wgT, s->d, s->E);
             int64_t items = (int64_t)s->T * (s->d / 4);

@@ -125,7 +125,8 @@ def test_a_bad_table_is_reported_and_stays_in_bounds(what):
     assert host(rop).tolist() == r_rop.tolist() and host(por).tolist() == r_por.tolist()
 
 
-@pytest.mark.parametrize("T,d,f,E,k,N,C,Dn,rank", [(600, 256, 384, 8, 2, 8, 2, 4, 3), (1500, 512, 256, 16, 4, 16, 4, 8, 9)])
+@pytest.mark.parametrize("T,d,f,E,k,N,C,Dn,rank", [(600, 256, 384, 8, 2, 8, 2, 4, 3), (1500, 512, 256, 16, 4, 16, 4, 8, 9),
+                          (900, 128, 128, 64, 4, 32, 8, 8, 3)])   # the last one: G = 256 groups, the most the tables hold
 def test_layer_over_replica_groups(T, d, f, E, k, N, C, Dn, rank):
     """permute_lite -> grouped FFN over groups -> combine gives the bits of permute -> grouped FFN -> combine,
     and both sit within the bf16 bar of the oracle's layer."""

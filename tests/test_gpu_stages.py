@@ -20,6 +20,7 @@ CASES = {
     "bf16_one_expert": dict(T=130, d=128, f=256, E=1, k=1, dtype="bf16", alpha=0.0, dead=0),
     "bf16_k_eq_E": dict(T=70, d=64, f=72, E=3, k=3, dtype="bf16", alpha=0.5, dead=0),
     "bf16_e130": dict(T=257, d=256, f=128, E=130, k=8, dtype="bf16", alpha=0.3, dead=0),
+    "bf16_e256": dict(T=400, d=256, f=64, E=256, k=8, dtype="bf16", alpha=0.2, dead=0),   # the largest expert count
     "bf16_e64_wide": dict(T=700, d=512, f=320, E=64, k=4, dtype="bf16", alpha=0.4, dead=2),
     "f32_ragged": dict(T=150, d=68, f=100, E=5, k=2, dtype="f32", alpha=1.0, dead=1),
     "f32_tiny_T": dict(T=1, d=8, f=4, E=2, k=1, dtype="f32", alpha=0.0, dead=0),
