@@ -163,6 +163,20 @@ struct LiteTables {          // in the workspace, written by the scan, read by t
     int32_t* ok;             // [1]
 };
 
+// exclusive prefix sum of v[0..255] over the 256 threads of the workgroup (every thread calls it)
+__device__ __forceinline__ int32_t block_exclusive_scan_256(int32_t mine, int32_t* tmp) {
+    const int t = threadIdx.x;
+    tmp[t] = mine;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {
+        const int32_t add = t >= d ? tmp[t - d] : 0;
+        __syncthreads();
+        tmp[t] += add;
+        __syncthreads();
+    }
+    return tmp[t] - mine;
+}
+
 __global__ __launch_bounds__(256) void permute_scan_lite_kernel(const int32_t* __restrict__ chunk_hist,
                                                                 int32_t* __restrict__ chunk_base, int nchunks, int E,
                                                                 int G, int n_rep, int R,
@@ -172,16 +186,22 @@ __global__ __launch_bounds__(256) void permute_scan_lite_kernel(const int32_t* _
                                                                 int32_t* __restrict__ group_counts,
                                                                 int32_t* __restrict__ group_offsets, LiteTables tb,
                                                                 int32_t* __restrict__ table_errors) {
-    __shared__ int32_t cnt[MOE_MAX_EXPERTS];
-    __shared__ int32_t off[MOE_MAX_EXPERTS + 1];
+    __shared__ int32_t tmp[256];
     __shared__ int32_t listed[MOE_MAX_EXPERTS];
     __shared__ int32_t gcnt[MOE_MAX_EXPERTS];
     __shared__ int32_t bad;
     const int e = threadIdx.x;
     int32_t n = 0;
     if (e < E) {
-        for (int c = 0; c < nchunks; ++c) n += chunk_hist[(size_t)c * E + e];
-        cnt[e] = n;
+        int c = 0;
+        for (; c + 8 <= nchunks; c += 8) {
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) n += v[u];
+        }
+        for (; c < nchunks; ++c) n += chunk_hist[(size_t)c * E + e];
         expert_counts[e] = n;
     }
     listed[e] = 0;
@@ -206,43 +226,48 @@ __global__ __launch_bounds__(256) void permute_scan_lite_kernel(const int32_t* _
     }
     __syncthreads();
     const bool ok = bad == 0;
-    if (e == 0) {  // exclusive scan of the expert counts (the fallback order)
-        int32_t run = 0;
-        for (int i = 0; i < E; ++i) {
-            off[i] = run;
-            run += cnt[i];
-        }
-        off[E] = run;
+    const int32_t expert_off = block_exclusive_scan_256(e < E ? n : 0, tmp);  // the fallback order
+    if (e == 0) {
         tb.ok[0] = ok ? 1 : 0;
         if (table_errors) table_errors[0] = bad;
         if (!ok) gcnt[0] = R;
     }
-    if (e < E && ok) {
-        const int len = hi - lo;
-        const int b = len ? n / len : 0, rm = len ? n % len : 0;
-        for (int r = 0; r < len; ++r) gcnt[rep_group[lo + r]] = b + (r < rm ? 1 : 0);
-        tb.lo[e] = lo;
-        tb.base[e] = b;
-        tb.rem[e] = rm;
+    if (e < E) {
+        if (ok) {
+            const int len = hi - lo;
+            const int b = len ? n / len : 0, rm = len ? n % len : 0;
+            for (int r = 0; r < len; ++r) gcnt[rep_group[lo + r]] = b + (r < rm ? 1 : 0);
+            tb.lo[e] = lo;
+            tb.base[e] = b;
+            tb.rem[e] = rm;
+        } else {
+            tb.lo[e] = expert_off;
+            tb.base[e] = 0;
+            tb.rem[e] = 0;
+        }
     }
     __syncthreads();
-    if (e < E && !ok) {
-        tb.lo[e] = off[e];
-        tb.base[e] = 0;
-        tb.rem[e] = 0;
+    const int32_t mine = e < G ? gcnt[e] : 0;
+    const int32_t goff = block_exclusive_scan_256(mine, tmp);
+    if (e < G) {
+        group_counts[e] = mine;
+        group_offsets[e] = goff;
     }
-    if (e == 0) {
-        int32_t run = 0;
-        for (int g = 0; g < G; ++g) {
-            group_counts[g] = gcnt[g];
-            group_offsets[g] = run;
-            run += gcnt[g];
-        }
-        group_offsets[G] = run;
-    }
+    if (e == G - 1) group_offsets[G] = goff + mine;
     if (e < E) {  // rank of the first pair of every chunk inside its expert
         int32_t run = 0;
-        for (int c = 0; c < nchunks; ++c) {
+        int c = 0;
+        for (; c + 8 <= nchunks; c += 8) {
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                chunk_base[(size_t)(c + u) * E + e] = run;
+                run += v[u];
+            }
+        }
+        for (; c < nchunks; ++c) {
             chunk_base[(size_t)c * E + e] = run;
             run += chunk_hist[(size_t)c * E + e];
         }
