@@ -80,8 +80,15 @@ def dispatcher_leg(w, s, g, buf, counts, N=32, D=8):
     A, T_model, best = P.moe_plan_expert_layout(ps, cost, Rm, 2, w.seed)
     planner_ms = (time.perf_counter() - t0) * 1e3
     received = P.moe_plan_lite_routing(ps, Rm, A).sum(axis=(0, 1))
+    # static expert parallelism for comparison: EP groups of E/C consecutive devices, device i holds the C
+    # experts of its position in the group (the same layout on every group)
     static = np.zeros((N, w.E), np.int32)
-    static[np.arange(w.E) % N, np.arange(w.E)] = 1
+    if w.E % C == 0 and N % (w.E // C) == 0:
+        for i in range(N):
+            p_ep = w.E // C
+            static[i, (i % p_ep) * C:(i % p_ep) * C + C] = 1
+    else:
+        static[np.arange(w.E) % N, np.arange(w.E)] = 1
     received_static = P.moe_plan_lite_routing(ps, Rm, static).sum(axis=(0, 1))
     G, eog, dog, rb, rg = P.moe_plan_dispatch_table(ps, A, 0)
     dev = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")
@@ -114,6 +121,53 @@ def dispatcher_leg(w, s, g, buf, counts, N=32, D=8):
                                                                     "after_relayout": float(received.max() / received.mean())},
             "permute_lite_ms": round(perm_ms, 4), "ffn_fwd_groups_ms": round(ffn_ms, 4),
             "table_errors": int(err.item())}
+
+
+def fsep_leg(w, counts, N=8, D=8):
+    """The FSEP parameter layout kernels on this workload's expert size, for the buffers of N ranks held
+    in this GPU's memory (one node of the paper's testbed): unshard restores C experts per rank, reshard
+    reduces their gradients back to shards.  GB/s = bytes read + written / time."""
+    import numpy as np
+    import torch
+    from paper_2602_11686_amd import fsep as F
+    from paper_2602_11686_amd import planner as P
+    C = max(1, 2 * w.E // N)
+    psi = 3 * w.d * w.f
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    el = 2 if w.dtype == "bf16" else 4
+    ps = P.PlanShape(N, w.E, C, D)
+    rng = np.random.default_rng(w.seed)
+    Rm = rng.poisson(np.maximum(counts, 1)[None, :] * rng.uniform(0.7, 1.3, size=(N, 1))).astype(np.int64)
+    cost = P.PlanCost(v_comm=2.0 * w.d, b_intra=64e9, b_inter=25e9, v_comp=6.0 * w.d * w.f, b_comp=1e15, f_ckpt=0)
+    A, _, _ = P.moe_plan_expert_layout(ps, cost, Rm, 2, w.seed)
+    hosted = np.full((N, C), -1, np.int32)
+    for i in range(N):
+        hosted[i, :A[i].sum()] = np.repeat(np.arange(w.E), A[i])
+    hd = torch.tensor(hosted, device="cuda")
+    shards = torch.zeros(N, w.E, psi // N, dtype=dt, device="cuda")
+    restored = torch.empty(N, C, psi, dtype=dt, device="cuda")
+    gsh = torch.empty(N, w.E, psi // N, dtype=dt, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, n=5):
+        fn()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    un_ms = timed(lambda: F.moe_fsep_unshard(shards, hd, restored))
+    restored.normal_()
+    re_ms = timed(lambda: F.moe_fsep_reshard(restored, hd, gsh))
+    slots = int((hosted >= 0).sum())
+    return {"ranks": N, "C": C, "psi": psi, "unshard_ms": round(un_ms, 4),
+            "unshard_gbs": round(2.0 * slots * psi * el / (un_ms * 1e-3) / 1e9, 1),
+            "reshard_ms": round(re_ms, 4),
+            "reshard_gbs": round((slots + w.E) * psi * el / (re_ms * 1e-3) / 1e9, 1),
+            "v_fsep_bytes_per_rank": C * (N - 1) * (psi // N) * el}
 
 
 def main():
@@ -237,6 +291,7 @@ def main():
         "stages": stages,
     }
     out["dispatcher"] = dispatcher_leg(w, s, g, buf, counts)
+    out["fsep_layout"] = fsep_leg(w, counts)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))

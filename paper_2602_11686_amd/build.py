@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["moe_api.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip"]
+SOURCES = ["moe_api.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip", "moe_fsep.hip"]
 HOST_SOURCES = ["moe_planner.cpp"]  # host-only C++ (the CPU planner), compiled with g++
 HOST_FLAGS = ["-O2", "-fPIC", "-std=c++17", "-ffp-contract=off", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,

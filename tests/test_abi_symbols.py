@@ -33,6 +33,10 @@ def test_library_exports_every_declared_symbol():
     for n in declared_functions("moe_planner.h"):
         assert hasattr(L, n), n
     assert sorted(planner.PLANNER_EXPORTS) == declared_functions("moe_planner.h")
+    from paper_2602_11686_amd import fsep
+    for n in declared_functions("moe_fsep.h"):
+        assert hasattr(L, n), n
+    assert sorted(fsep.FSEP_EXPORTS) == declared_functions("moe_fsep.h")
 
 
 def test_host_side_validation_needs_no_gpu():
