@@ -58,6 +58,37 @@ def cpu_baseline(w, inp, target_seconds=15.0):
                       f"{'fwd+bwd' if w.backward else 'fwd'}, fp32 oracle, {reps} pass(es), {total:.1f} s"}
 
 
+def cold_leg(w, s, g, buf, perm_bytes, comb_bytes, sets=4, rounds=6):
+    """permute and combine with their row buffers rotated over several sets (together well beyond the
+    256 MB memory-side cache plus the L2s), so that every call streams from and to HBM."""
+    import torch
+    from paper_2602_11686_amd import binding as B
+    xs = [torch.empty_like(g["x"]).copy_(g["x"]) for _ in range(sets)]
+    xps = [torch.empty_like(buf.x_perm) for _ in range(sets)]
+    ys = [torch.empty_like(buf.y) for _ in range(sets)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        for q in range(sets):
+            fn(q)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for r in range(rounds):
+            for q in range(sets):
+                fn(q)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (rounds * sets)
+
+    p_ms = timed(lambda q: B.moe_permute(s, xs[q], buf.topk_ids, buf.counts, buf.offsets, buf.row_of_pair,
+                                         buf.pair_of_row, xps[q], buf.ws))
+    c_ms = timed(lambda q: B.moe_unpermute_combine(s, xps[q], buf.row_of_pair, buf.topk_w, ys[q]))
+    mb = sets * (xs[0].numel() + xps[0].numel() + ys[0].numel()) * xs[0].element_size() / 1e6
+    return {"buffer_sets": sets, "rotated_MB": round(mb, 1),
+            "permute": {"ms": round(p_ms, 4), "gbs": round(perm_bytes / (p_ms * 1e-3) / 1e9, 1)},
+            "combine": {"ms": round(c_ms, 4), "gbs": round(comb_bytes / (c_ms * 1e-3) / 1e9, 1)}}
+
+
 def dispatcher_leg(w, s, g, buf, counts, N=32, D=8):
     """The planner and the token dispatcher on this workload's routing, for a synthetic cluster of N devices
     in nodes of D (the paper's testbed: 4 nodes of 8): layout search on the host (C++), then the permutation
@@ -290,6 +321,7 @@ def main():
                      "flops_per_launch": flops, "ms_per_launch": ffn_ms},
         "stages": stages,
     }
+    out["cold_cache"] = cold_leg(w, s, g, buf, perm_bytes, comb_bytes)
     out["dispatcher"] = dispatcher_leg(w, s, g, buf, counts)
     out["fsep_layout"] = fsep_leg(w, counts)
     if not args.no_cpu_baseline:
