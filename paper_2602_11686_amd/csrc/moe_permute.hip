@@ -20,7 +20,7 @@
 
 namespace moe {
 
-constexpr int kChunk = 512;        // pairs per wavefront in the sort
+constexpr int kChunk = 128;        // pairs per wavefront in the sort
 constexpr int kWavesPerBlock = 4;  // 256 threads
 
 constexpr size_t kLiteTableBytes = (4 * MOE_MAX_EXPERTS + 64) * sizeof(int32_t);
@@ -53,59 +53,90 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __rest
 }
 
 // ---- 2. scan: chunk_base[c][e] = first row of chunk c for expert e ---------------------
-// One thread per expert.  Input and output are different arrays, so the loads of the two
-// passes do not wait for the stores and overlap each other.
+// 256 threads = P parts x E experts (P = 256 / E): part p of expert e owns a contiguous range of
+// chunks, sums it, and after the parts' sums and the experts' offsets are known writes the running
+// base of every chunk of its range.  Input and output are different arrays, so the loads of the
+// two passes do not wait for the stores.
+struct ScanParts {
+    int e, part, c_begin, c_end;  // this thread's expert and chunk range (empty for surplus threads)
+    int P;
+};
+__device__ __forceinline__ ScanParts scan_parts(int nchunks, int E) {
+    ScanParts sp;
+    sp.P = 256 / E;  // E <= 256
+    sp.e = threadIdx.x % E;
+    sp.part = threadIdx.x / E;
+    const int len = (nchunks + sp.P - 1) / sp.P;
+    sp.c_begin = sp.part < sp.P ? min(sp.part * len, nchunks) : 0;
+    sp.c_end = sp.part < sp.P ? min(sp.c_begin + len, nchunks) : 0;
+    return sp;
+}
+__device__ __forceinline__ int32_t scan_range_sum(const int32_t* __restrict__ chunk_hist, int E, const ScanParts& sp) {
+    int32_t run = 0;
+    int c = sp.c_begin;
+    for (; c + 8 <= sp.c_end; c += 8) {
+        int32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + sp.e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) run += v[u];
+    }
+    for (; c < sp.c_end; ++c) run += chunk_hist[(size_t)c * E + sp.e];
+    return run;
+}
+__device__ __forceinline__ void scan_range_write(const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ chunk_base,
+                                                 int E, const ScanParts& sp, int32_t run) {
+    int c = sp.c_begin;
+    for (; c + 8 <= sp.c_end; c += 8) {
+        int32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + sp.e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            chunk_base[(size_t)(c + u) * E + sp.e] = run;
+            run += v[u];
+        }
+    }
+    for (; c < sp.c_end; ++c) {
+        chunk_base[(size_t)c * E + sp.e] = run;
+        run += chunk_hist[(size_t)c * E + sp.e];
+    }
+}
+
 __global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __restrict__ chunk_hist,
                                                            int32_t* __restrict__ chunk_base, int nchunks, int E,
                                                            int32_t* __restrict__ counts,
                                                            int32_t* __restrict__ offsets) {
-    __shared__ int32_t cnt[MOE_MAX_EXPERTS];
+    __shared__ int32_t psum[256];                    // [part][expert]
     __shared__ int32_t off[MOE_MAX_EXPERTS + 1];
-    const int e = threadIdx.x;
-    if (e < E) {
-        int32_t run = 0;
-        int c = 0;
-        for (; c + 8 <= nchunks; c += 8) {
-            int32_t v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) run += v[u];
+    const ScanParts sp = scan_parts(nchunks, E);
+    psum[threadIdx.x] = sp.part < sp.P ? scan_range_sum(chunk_hist, E, sp) : 0;
+    __syncthreads();
+    int32_t before = 0, total = 0;                   // this expert: sum of the earlier parts, sum of all parts
+    if (sp.part < sp.P)
+        for (int p = 0; p < sp.P; ++p) {
+            const int32_t v = psum[p * E + sp.e];
+            if (p < sp.part) before += v;
+            total += v;
         }
-        for (; c < nchunks; ++c) run += chunk_hist[(size_t)c * E + e];
-        cnt[e] = run;
-        counts[e] = run;
+    __syncthreads();
+    if (sp.part == 0) {
+        psum[sp.e] = total;                           // reuse: per-expert counts
+        counts[sp.e] = total;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         int32_t run = 0;
         for (int i = 0; i < E; ++i) {
             off[i] = run;
-            run += cnt[i];
+            run += psum[i];
         }
         off[E] = run;
     }
     __syncthreads();
-    if (e < E) offsets[e] = off[e];
-    if (e == 0) offsets[E] = off[E];
-    if (e < E) {
-        int32_t run = off[e];
-        int c = 0;
-        for (; c + 8 <= nchunks; c += 8) {
-            int32_t v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                chunk_base[(size_t)(c + u) * E + e] = run;
-                run += v[u];
-            }
-        }
-        for (; c < nchunks; ++c) {
-            chunk_base[(size_t)c * E + e] = run;
-            run += chunk_hist[(size_t)c * E + e];
-        }
-    }
+    if (sp.part == 0) offsets[sp.e] = off[sp.e];
+    if (threadIdx.x == 0) offsets[E] = off[E];
+    if (sp.part < sp.P) scan_range_write(chunk_hist, chunk_base, E, sp, off[sp.e] + before);
 }
 
 // ---- 3. stable rank of every pair ---------------------------------------------------
@@ -191,17 +222,25 @@ __global__ __launch_bounds__(256) void permute_scan_lite_kernel(const int32_t* _
     __shared__ int32_t gcnt[MOE_MAX_EXPERTS];
     __shared__ int32_t bad;
     const int e = threadIdx.x;
+    const ScanParts sp = scan_parts(nchunks, E);
+    __shared__ int32_t psum[256];
+    __shared__ int32_t nexp[MOE_MAX_EXPERTS];
+    psum[threadIdx.x] = sp.part < sp.P ? scan_range_sum(chunk_hist, E, sp) : 0;
+    __syncthreads();
+    int32_t part_before = 0;
+    if (sp.part < sp.P) {
+        int32_t total = 0;
+        for (int p = 0; p < sp.P; ++p) {
+            const int32_t v = psum[p * E + sp.e];
+            if (p < sp.part) part_before += v;
+            total += v;
+        }
+        if (sp.part == 0) nexp[sp.e] = total;
+    }
+    __syncthreads();
     int32_t n = 0;
     if (e < E) {
-        int c = 0;
-        for (; c + 8 <= nchunks; c += 8) {
-            int32_t v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) n += v[u];
-        }
-        for (; c < nchunks; ++c) n += chunk_hist[(size_t)c * E + e];
+        n = nexp[e];
         expert_counts[e] = n;
     }
     listed[e] = 0;
@@ -254,24 +293,8 @@ __global__ __launch_bounds__(256) void permute_scan_lite_kernel(const int32_t* _
         group_offsets[e] = goff;
     }
     if (e == G - 1) group_offsets[G] = goff + mine;
-    if (e < E) {  // rank of the first pair of every chunk inside its expert
-        int32_t run = 0;
-        int c = 0;
-        for (; c + 8 <= nchunks; c += 8) {
-            int32_t v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                chunk_base[(size_t)(c + u) * E + e] = run;
-                run += v[u];
-            }
-        }
-        for (; c < nchunks; ++c) {
-            chunk_base[(size_t)c * E + e] = run;
-            run += chunk_hist[(size_t)c * E + e];
-        }
-    }
+    // rank of the first pair of every chunk inside its expert
+    if (sp.part < sp.P) scan_range_write(chunk_hist, chunk_base, E, sp, part_before);
 }
 
 __global__ __launch_bounds__(256) void permute_rank_lite_kernel(const int32_t* __restrict__ ids, int R, int E,
