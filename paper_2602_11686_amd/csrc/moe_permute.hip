@@ -72,8 +72,17 @@ __device__ __forceinline__ ScanParts scan_parts(int nchunks, int E) {
     return sp;
 }
 __device__ __forceinline__ int32_t scan_range_sum(const int32_t* __restrict__ chunk_hist, int E, const ScanParts& sp) {
+    // (the histograms were written by workgroups on other XCDs: every batch of loads pays a trip beyond
+    // this XCD's L2, so the batches are made long)
     int32_t run = 0;
     int c = sp.c_begin;
+    for (; c + 32 <= sp.c_end; c += 32) {
+        int32_t v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + sp.e];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) run += v[u];
+    }
     for (; c + 8 <= sp.c_end; c += 8) {
         int32_t v[8];
 #pragma unroll
@@ -87,6 +96,16 @@ __device__ __forceinline__ int32_t scan_range_sum(const int32_t* __restrict__ ch
 __device__ __forceinline__ void scan_range_write(const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ chunk_base,
                                                  int E, const ScanParts& sp, int32_t run) {
     int c = sp.c_begin;
+    for (; c + 32 <= sp.c_end; c += 32) {
+        int32_t v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + sp.e];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+            chunk_base[(size_t)(c + u) * E + sp.e] = run;
+            run += v[u];
+        }
+    }
     for (; c + 8 <= sp.c_end; c += 8) {
         int32_t v[8];
 #pragma unroll
