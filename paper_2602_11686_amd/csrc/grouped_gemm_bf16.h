@@ -470,13 +470,37 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                             static_cast<float*>(g.C0)[cbase + (int64_t)row * g.ldc + col] = acc[i][j][r];
                     }
                 }
-        } else if constexpr (EPI == EPI_DH) {
+        } else if constexpr (EPI == EPI_DH || EPI == EPI_ADD) {
             // dH in fp32 through LDS, 64 rows x 128 columns at a time; then 8 columns per thread: read A, B,
             // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).  Staging rows are 512 B; the
             // 16-byte piece index is XORed with 8*((row>>2)&1) so that the two lane halves hit different banks.
+            // The global operands of a pass (saved A and B, or the old C) are requested before the staging
+            // writes, so that they travel while the accumulators go through LDS.
+            constexpr int IPT = 64 * 16 / kThreads;  // 8-column items per thread and pass
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 for (int p = 0; p < 2; ++p) {
+                    u32x4 pre0[IPT], pre1[IPT];
+                    int64_t idxs[IPT];
+                    bool live[IPT];
+#pragma unroll
+                    for (int u = 0; u < IPT; ++u) {
+                        const int item = threadIdx.x + u * kThreads;
+                        const int sr = item >> 4, cg = item & 15;
+                        const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
+                        live[u] = grow < t.m_lim && gcol < g.N;
+                        idxs[u] = (int64_t)grow * g.ldc + gcol;
+                        pre0[u] = (u32x4){0, 0, 0, 0};
+                        pre1[u] = (u32x4){0, 0, 0, 0};
+                        if (live[u]) {
+                            if constexpr (EPI == EPI_ADD) {
+                                pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.C0) + idxs[u]);
+                            } else {
+                                pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + idxs[u]);
+                                pre1[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + idxs[u]);
+                            }
+                        }
+                    }
                     {
 #pragma unroll
                         for (int j = 0; j < NJ; ++j)
@@ -491,17 +515,28 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                             }
                     }
                     __syncthreads();
-                    for (int item = threadIdx.x; item < 64 * 16; item += kThreads) {
+#pragma unroll
+                    for (int u = 0; u < IPT; ++u) {
+                        if (!live[u]) continue;
+                        const int item = threadIdx.x + u * kThreads;
                         const int sr = item >> 4, cg = item & 15;
-                        const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
-                        if (grow < t.m_lim && gcol < g.N) {
-                            const int64_t idx = (int64_t)grow * g.ldc + gcol;
-                            const int sw = ((sr >> 2) & 1) << 3;
-                            const f32x4v d0 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg) ^ sw) * 16);
-                            const f32x4v d1 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg + 1) ^ sw) * 16);
-                            const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
-                            const u32x4 av = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + idx);
-                            const u32x4 bv = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + idx);
+                        const int64_t idx = idxs[u];
+                        const int sw = ((sr >> 2) & 1) << 3;
+                        const f32x4v d0 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg) ^ sw) * 16);
+                        const f32x4v d1 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg + 1) ^ sw) * 16);
+                        const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+                        if constexpr (EPI == EPI_ADD) {  // C += tile: the bf16 values plus the tile in fp32, one rounding
+                            const u32x4 old = pre0[u];
+                            u32x4 o;
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const float lo = __uint_as_float(old[q] << 16) + dh[2 * q];
+                                const float hi = __uint_as_float(old[q] & 0xFFFF0000u) + dh[2 * q + 1];
+                                o[q] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+                            }
+                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = o;
+                        } else {
+                            const u32x4 av = pre0[u], bv = pre1[u];
                             u32x4 oh, oa, ob;
 #pragma unroll
                             for (int q = 0; q < 4; ++q) {

@@ -29,7 +29,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-enum { EPI_STORE = 0, EPI_STORE2 = 1, EPI_SWIGLU = 2, EPI_DH = 3, EPI_STORE_F32 = 4 };
+enum { EPI_STORE = 0, EPI_STORE2 = 1, EPI_SWIGLU = 2, EPI_DH = 3, EPI_STORE_F32 = 4, EPI_ADD = 5 };
 
 struct Seg {
     const void* A;
@@ -404,6 +404,24 @@ void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, c
     g.lda = d; g.ldb = n_pad; g.strideC = (int64_t)d * n_pad;
     g.C0 = partial; g.ldc = n_pad;
     auto kern = gg256_kernel<1, 0, false, EPI_STORE_F32, true>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kGemmLds);
+        attr_done = true;
+    }
+    kern<<<dim3(256), kThreads, kGemmLds, st>>>(g);
+}
+
+void launch_gate_dx_gemm(const void* dl_hi, const void* dl_lo, const void* wg_pad, const int32_t* whole, int d, int n_pad,
+                         void* dx, hipStream_t st) {
+    GArgs g{};
+    g.offsets = whole; g.E = 1; g.N = d; g.K = n_pad; g.nseg = 2;
+    g.seg[0] = {dl_hi, wg_pad, nullptr};
+    g.seg[1] = {dl_lo, wg_pad, nullptr};
+    g.lda = n_pad; g.ldb = n_pad; g.strideB = 0;
+    g.C0 = dx; g.ldc = d;
+    auto kern = gg256_kernel<0, 1, false, EPI_ADD, false>;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
