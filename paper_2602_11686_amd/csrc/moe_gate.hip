@@ -120,12 +120,25 @@ typedef __bf16 gbf16x8 __attribute__((ext_vector_type(8)));
 typedef float gf32x16 __attribute__((ext_vector_type(16)));
 constexpr int kGateMT = 32;
 
-__global__ void gate_transpose_bf16_kernel(const bf16_t* __restrict__ wg, bf16_t* __restrict__ wgT, int d, int E,
-                                           int Epad) {
-    const int64_t n = (int64_t)d * Epad;
+// The gate weight in the order the MFMA lanes of gate_topk_mfma_kernel consume it ("fragment-major"): the
+// 64 lanes x 8 values of one B operand are 1 KB of consecutive memory, so that every operand load of a
+// wavefront is one fully coalesced 1 KB read (a plain transposed copy makes each lane read 16 bytes of a
+// different row: 32 cache lines per load instruction).  Block index: ((wavefront's K range, 64-wide chunk),
+// expert tile j, k-step s4); inside a block lane (l32, kg) holds expert j*32 + l32,
+// k = range*kq + chunk*64 + kg*32 + s4*8 + 0..7.  Experts past E are zero.
+__global__ void gate_pack_wg_kernel(const bf16_t* __restrict__ wg, bf16_t* __restrict__ wfrag, int d, int E, int NT,
+                                    int NW) {
+    const int64_t n = (int64_t)d * NT * 32;
+    const int kq = d / NW, nchunk = kq / 64;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        const int e = (int)(i / d), c = (int)(i - (int64_t)e * d);
-        wgT[i] = e < E ? wg[(size_t)c * E + e] : (bf16_t)0;
+        const int z = (int)(i & 7), lane = (int)((i >> 3) & 63), s4 = (int)((i >> 9) & 3);
+        const int64_t blk = i >> 11;  // (range*nchunk + chunk)*NT + j
+        const int j = (int)(blk % NT);
+        const int64_t rc = blk / NT;
+        const int ci = (int)(rc % nchunk), w = (int)(rc / nchunk);
+        const int e = j * 32 + (lane & 31);
+        const int k = w * kq + ci * 64 + (lane >> 5) * 32 + s4 * 8 + z;
+        wfrag[i] = e < E ? wg[(size_t)k * E + e] : (bf16_t)0;
     }
 }
 
@@ -192,7 +205,7 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(const bf16_t* _
     trow = trow < Tn ? trow : Tn - 1;
     const int kq = d / NW;
     const bf16_t* xa = x + (size_t)trow * d + wave * kq + kg * 32;
-    const bf16_t* wb = wgT + (size_t)l32 * d + wave * kq + kg * 32;
+    const bf16_t* wb = wgT + ((size_t)wave * (kq / 64) * NT) * 2048 + lane * 8;  // fragment-major, see gate_pack_wg_kernel
 
     gf32x16 acc[NT];
 #pragma unroll
@@ -210,7 +223,7 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(const bf16_t* _
         for (int j = 0; j < NT; ++j)
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4)
-                bb[j][s4] = *reinterpret_cast<const gbf16x8*>(wb + (size_t)j * 32 * d + c + s4 * 8);
+                bb[j][s4] = *reinterpret_cast<const gbf16x8*>(wb + (((size_t)(c >> 6) * NT + j) * 4 + s4) * 512);
     };
     auto mma_chunk = [&](const gbf16x8 (&aa)[4], const gbf16x8 (&bb)[NT][4]) {
 #pragma unroll
@@ -512,11 +525,11 @@ extern "C" moe_status moe_gate_topk(const moe_shape* s, const void* x, const voi
         const int nt = (s->E + 31) / 32;
         const int NT = nt <= 1 ? 1 : nt <= 2 ? 2 : nt <= 4 ? 4 : 8;
         bf16_t* wgT = static_cast<bf16_t*>(ws);
-        gate_transpose_bf16_kernel<<<256, 256, 0, st>>>(static_cast<const bf16_t*>(w_gate), wgT, s->d, s->E, NT * 32);
         const int grid = (s->T + kGateMT - 1) / kGateMT;
         // 8 wavefronts (the contraction split 8 ways) halve the chain of dependent loads of a 32-token tile;
         // the partial logits of 8 wavefronts fit the LDS up to 128 padded experts.
         const int NW = (s->d % 512 == 0 && NT <= 4) ? 8 : 4;
+        gate_pack_wg_kernel<<<256, 256, 0, st>>>(static_cast<const bf16_t*>(w_gate), wgT, s->d, s->E, NT, NW);
         size_t lds = (size_t)NW * kGateMT * NT * 32 * sizeof(float);            // partial logits
         if (lds < (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float)) lds = (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float);
 #define MOE_GATE_LAUNCH(N, W)                                                                                      \
