@@ -197,6 +197,7 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(const bf16_t* _
                                                              int Tn, int d, int E, int k) {
     extern __shared__ float part[];  // [NW][32][NT*32] partial logits, then the picked logits [32][MOE_MAX_EXPERTS]
     constexpr int TPW = kGateMT / NW;  // tokens finished by each wavefront
+    constexpr int NE = (NT * 32 + 63) / 64;  // experts per lane in the top-k phase
     constexpr int EP = NT * 32;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, kg = lane >> 5;
@@ -251,12 +252,12 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(const bf16_t* _
         }
     __syncthreads();
     // wave w finishes tokens TPW*w .. TPW*w + TPW-1; lane owns experts lane, lane+64, ...
-    float vals[TPW][kGateMaxNE];
+    float vals[TPW][NE];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
         const int row = wave * TPW + i;
 #pragma unroll
-        for (int j = 0; j < kGateMaxNE; ++j) {
+        for (int j = 0; j < NE; ++j) {
             const int e = lane + 64 * j;
             float v = -INFINITY;
             if (e < E) {
@@ -276,7 +277,7 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(const bf16_t* _
         for (int i = 0; i < TPW; ++i) {
             const int t = t0 + wave * TPW + i;
 #pragma unroll
-            for (int j = 0; j < kGateMaxNE; ++j)
+            for (int j = 0; j < NE; ++j)
                 if (t < Tn && lane + 64 * j < E) logits_out[(size_t)t * E + lane + 64 * j] = vals[i][j];
         }
     }
@@ -285,18 +286,18 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(const bf16_t* _
         for (int i = 0; i < TPW; ++i) {
             float lv = vals[i][0];
 #pragma unroll
-            for (int j = 1; j < kGateMaxNE; ++j) lv = fmaxf(lv, vals[i][j]);
+            for (int j = 1; j < NE; ++j) lv = fmaxf(lv, vals[i][j]);
             const float m = wave_max_f32(lv);  // uniform
             // lowest expert index holding the maximum: experts are laid out e = lane + 64*j
             int be = -1;
 #pragma unroll
-            for (int j = kGateMaxNE - 1; j >= 0; --j) {
+            for (int j = NE - 1; j >= 0; --j) {
                 const uint64_t bal = __ballot(vals[i][j] == m);
                 if (bal) be = 64 * j + __builtin_ctzll(bal);
             }
             if ((be & 63) == lane) {
 #pragma unroll
-                for (int j = 0; j < kGateMaxNE; ++j)
+                for (int j = 0; j < NE; ++j)
                     if (be == lane + 64 * j) vals[i][j] = -INFINITY;
             }
             const int t = t0 + wave * TPW + i;
