@@ -528,8 +528,8 @@ extern "C" moe_status moe_gate_topk(const moe_shape* s, const void* x, const voi
         bf16_t* wgT = static_cast<bf16_t*>(ws);
         const int grid = (s->T + kGateMT - 1) / kGateMT;
         // 8 wavefronts (the contraction split 8 ways) halve the chain of dependent loads of a 32-token tile;
-        // the partial logits of 8 wavefronts fit the LDS up to 128 padded experts.
-        const int NW = (s->d % 512 == 0 && NT <= 4) ? 8 : 4;
+        // from 128 padded experts on, 4 wavefronts and half the partial-sum area (two workgroups per CU) do better.
+        const int NW = (s->d % 512 == 0 && NT <= 2) ? 8 : 4;
         gate_pack_wg_kernel<<<256, 256, 0, st>>>(static_cast<const bf16_t*>(w_gate), wgT, s->d, s->E, NT, NW);
         size_t lds = (size_t)NW * kGateMT * NT * 32 * sizeof(float);            // partial logits
         if (lds < (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float)) lds = (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float);
