@@ -208,6 +208,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2_e64k4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hot-path-only", action="store_true",
+                    help="time the layer only: no cold-cache, dispatcher, FSEP or CPU legs (what the profiles are taken on)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -321,10 +323,11 @@ def main():
                      "flops_per_launch": flops, "ms_per_launch": ffn_ms},
         "stages": stages,
     }
-    out["cold_cache"] = cold_leg(w, s, g, buf, perm_bytes, comb_bytes)
-    out["dispatcher"] = dispatcher_leg(w, s, g, buf, counts)
-    out["fsep_layout"] = fsep_leg(w, counts)
-    if not args.no_cpu_baseline:
+    if not args.hot_path_only:
+        out["cold_cache"] = cold_leg(w, s, g, buf, perm_bytes, comb_bytes)
+        out["dispatcher"] = dispatcher_leg(w, s, g, buf, counts)
+        out["fsep_layout"] = fsep_leg(w, counts)
+    if not args.no_cpu_baseline and not args.hot_path_only:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))
 

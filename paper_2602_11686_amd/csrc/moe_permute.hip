@@ -20,12 +20,18 @@
 
 namespace moe {
 
-constexpr int kChunk = 128;        // pairs per wavefront in the sort
+// pairs per wavefront in the sort: 128, doubled until there are at most 256 chunks (the scan walks the
+// chunks of an expert one after the other; short chunks keep the histogram and rank kernels parallel)
+static inline int chunk_pairs(int64_t R) {
+    int c = 128;
+    while ((R + c - 1) / c > 256 && c < 8192) c *= 2;
+    return c;
+}
 constexpr int kWavesPerBlock = 4;  // 256 threads
 
 constexpr size_t kLiteTableBytes = (4 * MOE_MAX_EXPERTS + 64) * sizeof(int32_t);
 
-static inline int num_chunks(int64_t R) { return (int)((R + kChunk - 1) / kChunk); }
+static inline int num_chunks(int64_t R) { const int c = chunk_pairs(R); return (int)((R + c - 1) / c); }
 
 size_t permute_workspace_bytes(const moe_shape* s) {
     const int64_t R = (int64_t)s->T * s->k;
@@ -34,7 +40,7 @@ size_t permute_workspace_bytes(const moe_shape* s) {
 }
 
 // ---- 1. per-chunk histogram ---------------------------------------------------
-__global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __restrict__ ids, int R, int E,
+__global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __restrict__ ids, int R, int E, int kChunk,
                                                            int32_t* __restrict__ chunk_hist) {
     extern __shared__ int32_t lds_hist[];  // [kWavesPerBlock][E]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __rest
 }
 
 // ---- 3. stable rank of every pair ---------------------------------------------------
-__global__ __launch_bounds__(256) void permute_rank_kernel(const int32_t* __restrict__ ids, int R, int E,
+__global__ __launch_bounds__(256) void permute_rank_kernel(const int32_t* __restrict__ ids, int R, int E, int kChunk,
                                                            const int32_t* __restrict__ chunk_base,
                                                            int32_t* __restrict__ row_of_pair,
                                                            int32_t* __restrict__ pair_of_row) {
@@ -316,7 +322,7 @@ __global__ __launch_bounds__(256) void permute_scan_lite_kernel(const int32_t* _
     if (sp.part < sp.P) scan_range_write(chunk_hist, chunk_base, E, sp, part_before);
 }
 
-__global__ __launch_bounds__(256) void permute_rank_lite_kernel(const int32_t* __restrict__ ids, int R, int E,
+__global__ __launch_bounds__(256) void permute_rank_lite_kernel(const int32_t* __restrict__ ids, int R, int E, int kChunk,
                                                                 const int32_t* __restrict__ chunk_base,
                                                                 const int32_t* __restrict__ rep_group,
                                                                 const int32_t* __restrict__ group_offsets,
@@ -521,9 +527,9 @@ extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32
     int32_t* chunk_hist = static_cast<int32_t*>(ws);
     int32_t* chunk_base = chunk_hist + align_up((size_t)nchunks * E * sizeof(int32_t), 256) / sizeof(int32_t);
     const size_t lds = (size_t)kWavesPerBlock * E * sizeof(int32_t);
-    permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_hist);
+    permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_pairs(R), chunk_hist);
     permute_scan_kernel<<<1, 256, 0, st>>>(chunk_hist, chunk_base, nchunks, E, counts, offsets);
-    permute_rank_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_base, row_of_pair, pair_of_row);
+    permute_rank_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_pairs(R), chunk_base, row_of_pair, pair_of_row);
     if (x_perm) {
         const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
         const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);
@@ -569,11 +575,11 @@ extern "C" moe_status moe_permute_lite(const moe_shape* s, int32_t G, int32_t n_
     int32_t* chunk_base = chunk_hist + hist_ints;
     int32_t* tables = chunk_base + hist_ints;
     LiteTables tb{tables, tables + MOE_MAX_EXPERTS, tables + 2 * MOE_MAX_EXPERTS, tables + 4 * MOE_MAX_EXPERTS};
-    permute_hist_kernel<<<nblocks, 256, (size_t)kWavesPerBlock * E * sizeof(int32_t), st>>>(topk_ids, R, E, chunk_hist);
+    permute_hist_kernel<<<nblocks, 256, (size_t)kWavesPerBlock * E * sizeof(int32_t), st>>>(topk_ids, R, E, chunk_pairs(R), chunk_hist);
     permute_scan_lite_kernel<<<1, 256, 0, st>>>(chunk_hist, chunk_base, nchunks, E, G, n_rep, R, rep_begin, rep_group,
                                                 expert_counts, group_counts, group_offsets, tb, table_errors);
     permute_rank_lite_kernel<<<nblocks, 256, (size_t)kWavesPerBlock * 4 * E * sizeof(int32_t), st>>>(
-        topk_ids, R, E, chunk_base, rep_group, group_offsets, tb, row_of_pair, pair_of_row);
+        topk_ids, R, E, chunk_pairs(R), chunk_base, rep_group, group_offsets, tb, row_of_pair, pair_of_row);
     if (x_perm) {
         const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
         const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);
