@@ -685,30 +685,19 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             // (the youngest 4*CPW loads belong to stages it+2 and it+3)
             asm volatile(MOE_VMCNT(MOE_VM2) " lgkmcnt(0)" ::: "memory");
             __syncthreads();
-            if constexpr (RAGK) {
-                // wgrad: the stage's DMA instructions go out in one burst right behind the barrier.  Dealt out
-                // between the MFMAs (as below) the workgroups of an XCD drift apart in their requests for the
-                // panels they share, and the traffic beyond L2 of the two-matrix wgrad triples (measured:
-                // 37.6 GB against 11.5 GB per launch on the Mixtral-shaped layer, 5 % more time).
-                issue(it + kStages, it & (kStages - 1));
-                load_frags(nx, 0, fa[0], fb[0]);
-                mma(fa[1], fb[1]);
-                interleave_mfma_dsread<kPairs>();
-            } else {
-                // second k-step: the DMA instructions of stage it+4 (and their address arithmetic) are dealt
-                // out between the MFMAs, a quarter after each row of MFMA blocks, so that the matrix pipe stays
-                // fed while they issue; the pins keep each row of MFMAs in front of its quarter.
-                load_frags(nx, 0, fa[0], fb[0]);
+            // second k-step: the DMA instructions of stage it+4 (and their address arithmetic) are dealt out
+            // between the MFMAs, a quarter after each row of MFMA blocks, so that the matrix pipe stays fed
+            // while they issue; the pins keep each row of MFMAs in front of its quarter.
+            load_frags(nx, 0, fa[0], fb[0]);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 4; ++i) {
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
-                        pin_one(acc[i][j]);
-                    }
-                    issue_part(it + kStages, it & (kStages - 1), i * (CPW / 2), (i + 1) * (CPW / 2));
-                    if (i < 3) pin_one(acc[i + 1][0]);  // the next row's MFMAs read this value: they stay behind the DMA
+                for (int j = 0; j < NJ; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+                    pin_one(acc[i][j]);
                 }
+                issue_part(it + kStages, it & (kStages - 1), i * (CPW / 2), (i + 1) * (CPW / 2));
+                if (i < 3) pin_one(acc[i + 1][0]);  // the next row's MFMAs read this value: they stay behind the DMA
             }
         }
         // ---- the last (up to four) stages: nothing left to issue for this tile ----
