@@ -126,9 +126,15 @@ __device__ __forceinline__ int logical_tile(int wg) {
     return (((idx >> 5) * 8 + xcd) << 5) + (idx & 31);
 }
 
+template <int N>
+struct IntTag {
+    static constexpr int value = N;
+};
+
 struct TileDesc {
     int e, m0, m_lim, n0, kbeg, kend, nk;  // nk = k-stages per K segment
     bool valid;
+    bool half;  // ragged M: at most TM/2 live rows (the tail of an expert): computed as a 128 x 256 tile
 };
 
 // The kernel is persistent: one workgroup per CU walks the tiles  logical_tile(blockIdx.x + r *
@@ -183,6 +189,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         const int L = logical_tile(blockIdx.x + round * gridDim.x);
         t.valid = L < total_tiles;
         t.e = 0; t.m0 = 0; t.m_lim = 0; t.n0 = 0; t.kbeg = 0; t.kend = 0; t.nk = 0;
+        t.half = false;
         if (!t.valid) return t;
         int m, nt;
         if constexpr (RAGK) {
@@ -219,6 +226,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         t.kbeg = __builtin_amdgcn_readfirstlane(t.kbeg);
         t.kend = __builtin_amdgcn_readfirstlane(t.kend);
         t.nk = __builtin_amdgcn_readfirstlane(t.nk);
+        if constexpr (!RAGK && kWaves == 8) t.half = t.m_lim - t.m0 <= TM / 2;
         return t;
     };
 
@@ -229,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     // row form: chunk c = wave*2 + i covers rows 16c .. 16c+15; lane -> row 16c + lane/4, slot lane%4
     // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
     TileDesc di;                  // tile whose stages are being issued
-    di.valid = false; di.e = 0; di.m0 = 0; di.m_lim = 0; di.n0 = 0; di.kbeg = 0; di.kend = 0; di.nk = 0;
+    di.valid = false; di.half = false; di.e = 0; di.m0 = 0; di.m_lim = 0; di.n0 = 0; di.kbeg = 0; di.kend = 0; di.nk = 0;
     // Ragged M: per-lane byte offsets of this lane's 16-byte pieces relative to a wave-uniform base of the tile
     // (sA / sB per K segment; pB for the two-matrix B tile, whose lanes read from two allocations).
     // Ragged K: element offsets (k-independent part), full addresses are formed per load.
@@ -373,8 +381,12 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     }
     // fragments of k-step kk of a stage -> registers.  B first: the MFMAs below walk a[0] x b[0..1],
     // a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
-    auto load_frags = [&](const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[NJ]) {
+    // NI = row blocks per wavefront: 4 (128 x 64 per wavefront, 256-row tile) or 2 (64 x 64, 128-row tile:
+    // wavefront row wm then starts at row 64*wm, which `a_shift` = wm*64 rows takes off the A offsets).
+    auto load_frags = [&](auto ni_tag, const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[NJ]) {
+        constexpr int NI = decltype(ni_tag)::value;
         const char* sb = st + kBOff;
+        if constexpr (NI == 2 && AT == 0) st -= wm * 64 * 64;
         const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
@@ -388,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NI; ++i) {
             if constexpr (AT == 0) {
                 a[i] = *reinterpret_cast<const bf16x8*>(st + a_rd[i] + rowform);
             } else {
@@ -408,9 +420,10 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     };
-    auto mma = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[NJ]) {
+    auto mma = [&](auto ni_tag, const bf16x8 (&a)[4], const bf16x8 (&b)[NJ]) {
+        constexpr int NI = decltype(ni_tag)::value;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
@@ -422,14 +435,13 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         if constexpr (kWaves == 8) asm volatile("" : "+v"(v));  // 256 registers per lane: all of them VGPRs
         else asm volatile("" : "+a"(v));                        // 512: accumulators in AGPRs
     };
-    auto pin_acc = [&]() {
+    auto pin_acc = [&](auto ni_tag) {
+        constexpr int NI = decltype(ni_tag)::value;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int j = 0; j < NJ; ++j) pin_one(acc[i][j]);
     };
-    constexpr int kReads = (AT == 0 ? 4 : 8) + (BT == 1 ? NJ : 2 * NJ);
-    constexpr int kPairs = kReads > 4 * NJ ? kReads : 4 * NJ;  // MFMA / LDS-read pairs to interleave per k-step
 
     // ---- epilogue of one tile.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
     // inside a 32x32 block) go through LDS, 64 rows at a time (block i of both wavefront rows), so that
@@ -457,12 +469,16 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     };
     auto epilogue = [&](const TileDesc& t, char* stg) {
         const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
+        // a 128-row tile holds two row blocks per wavefront, the rows of wavefront row 1 start at 64
+        const bool half = !RAGK && kWaves == 8 && t.half;
+        const int ni = half ? 2 : 4, wrows = half ? 64 : 128;
         if constexpr (EPI == EPI_STORE_F32) {  // narrow fp32 output (gate weight gradient): direct stores
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = t.m0 + wm * 128 + i * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+                    if (i >= ni) continue;
+                    const int row = t.m0 + wm * wrows + i * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) {
                         const int col = t.n0 + wn * NJ * 32 + j * 32 + l32;
@@ -475,10 +491,15 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).  Staging rows are 512 B; the
             // 16-byte piece index is XORed with 8*((row>>2)&1) so that the two lane halves hit different banks.
             // The global operands of a pass (saved A and B, or the old C) are requested before the staging
-            // writes, so that they travel while the accumulators go through LDS.
+            // writes, so that they travel while the accumulators go through LDS.  Every lane loads (dead items
+            // from a clamped address) and every lane consumes what it loaded; only the stores are predicated.
+            // A load skipped or left unconsumed on some path would count as pending at the top of the next
+            // tile's main loop, where the compiler then waits for ALL outstanding loads, the DMA ones included.
             constexpr int IPT = 64 * 16 / kThreads;  // 8-column items per thread and pass
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
+                // (a 128-row tile runs the passes of row blocks 2 and 3 with every item masked: cheaper than
+                // a branch around the pass, which costs the 256-row tiles their load/store overlap)
                 for (int p = 0; p < 2; ++p) {
                     u32x4 pre0[IPT], pre1[IPT];
                     int64_t idxs[IPT];
@@ -487,18 +508,17 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                     for (int u = 0; u < IPT; ++u) {
                         const int item = threadIdx.x + u * kThreads;
                         const int sr = item >> 4, cg = item & 15;
-                        const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
-                        live[u] = grow < t.m_lim && gcol < g.N;
+                        const int grow = t.m0 + (sr >> 5) * wrows + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
+                        live[u] = grow < t.m_lim && gcol < g.N && i < ni;
+                        const int lrow = grow < t.m_lim ? grow : t.m_lim - 1, lcol = gcol < g.N ? gcol : g.N - 8;
                         idxs[u] = (int64_t)grow * g.ldc + gcol;
-                        pre0[u] = (u32x4){0, 0, 0, 0};
-                        pre1[u] = (u32x4){0, 0, 0, 0};
-                        if (live[u]) {
-                            if constexpr (EPI == EPI_ADD) {
-                                pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.C0) + idxs[u]);
-                            } else {
-                                pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + idxs[u]);
-                                pre1[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + idxs[u]);
-                            }
+                        const int64_t lidx = (int64_t)lrow * g.ldc + lcol;
+                        if constexpr (EPI == EPI_ADD) {
+                            pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.C0) + lidx);
+                            pre1[u] = (u32x4){0, 0, 0, 0};
+                        } else {
+                            pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + lidx);
+                            pre1[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + lidx);
                         }
                     }
                     {
@@ -515,9 +535,12 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                             }
                     }
                     __syncthreads();
+                    // vmcnt(0) on every path and visible to the compiler (a builtin, not inline assembly): the
+                    // arithmetic below only feeds predicated stores, so the compiler sinks it, and the wait for
+                    // the loads with it, under the predicate
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
                     for (int u = 0; u < IPT; ++u) {
-                        if (!live[u]) continue;
                         const int item = threadIdx.x + u * kThreads;
                         const int sr = item >> 4, cg = item & 15;
                         const int64_t idx = idxs[u];
@@ -534,7 +557,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                                 const float hi = __uint_as_float(old[q] & 0xFFFF0000u) + dh[2 * q + 1];
                                 o[q] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
                             }
-                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = o;
+                            if (live[u]) *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = o;
                         } else {
                             const u32x4 av = pre0[u], bv = pre1[u];
                             u32x4 oh, oa, ob;
@@ -554,9 +577,11 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                                 oa[q] = (uint32_t)f32_to_bf16(da[0]) | ((uint32_t)f32_to_bf16(da[1]) << 16);
                                 ob[q] = (uint32_t)f32_to_bf16(db[0]) | ((uint32_t)f32_to_bf16(db[1]) << 16);
                             }
-                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = oh;
-                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = oa;
-                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = ob;
+                            if (live[u]) {
+                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = oh;
+                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = oa;
+                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = ob;
+                            }
                         }
                     }
                     __syncthreads();
@@ -589,7 +614,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                 __syncthreads();
                 for (int item = threadIdx.x; item < 64 * PPR; item += kThreads) {
                     const int sr = item / PPR, pc = item - sr * PPR;
-                    const int grow = t.m0 + (sr >> 5) * 128 + i * 32 + (sr & 31);
+                    const int grow = t.m0 + (sr >> 5) * wrows + i * 32 + (sr & 31);
                     int col = pc * 8;
                     bf16_t* dst = dst0;
                     if (dst1 && col >= cols0) { col -= cols0; dst = dst1; }
@@ -602,6 +627,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             };
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
+                if (i >= ni) break;
                 if constexpr (EPI == EPI_SWIGLU) {
                     for (int pass = 0; pass < (g.S0 ? 3 : 1); ++pass) {
 #pragma unroll
@@ -664,57 +690,70 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         const int tot0 = t.nk * g.nseg;
         for (int q = 0; q < kStages && q < tot0; ++q) issue(q, q);
     }
-    for (;;) {
-        const int total = t.nk * g.nseg;
-        zero_acc();
+    // The main loop of one tile; NI as in load_frags.
+    auto run_tile = [&](auto ni_tag, const int total) {
+        constexpr int NI = decltype(ni_tag)::value;
+        constexpr int kReads = (AT == 0 ? NI : 2 * NI) + (BT == 1 ? NJ : 2 * NJ);
+        constexpr int kPairs = kReads > NI * NJ ? kReads : NI * NJ;  // MFMA / LDS-read pairs to interleave per k-step
+        constexpr int kDeal = 2 * CPW / NI;                         // DMA instructions behind each row of MFMAs
         // stage 0 must have landed: it is followed by min(total, 4) - 1 younger stage loads
         if (total >= 4) asm volatile(MOE_VMCNT(MOE_VM3) ::: "memory");
         else wait_loads(total - 1);
         __syncthreads();
-        load_frags(smem, 0, fa[0], fb[0]);
+        load_frags(ni_tag, smem, 0, fa[0], fb[0]);
         int it = 0;
         // ---- hot loop: branch-free ----
         for (; it + kStages < total; ++it) {
             const char* st = smem + (it & (kStages - 1)) * kStageBytes;
             const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
-            load_frags(st, 1, fa[1], fb[1]);
-            mma(fa[0], fb[0]);
+            load_frags(ni_tag, st, 1, fa[1], fb[1]);
+            mma(ni_tag, fa[0], fb[0]);
             interleave_mfma_dsread<kPairs>();
-            pin_acc();
+            pin_acc(ni_tag);
             // this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
             // (the youngest 4*CPW loads belong to stages it+2 and it+3)
             asm volatile(MOE_VMCNT(MOE_VM2) " lgkmcnt(0)" ::: "memory");
             __syncthreads();
             // second k-step: the DMA instructions of stage it+4 (and their address arithmetic) are dealt out
-            // between the MFMAs, a quarter after each row of MFMA blocks, so that the matrix pipe stays fed
-            // while they issue; the pins keep each row of MFMAs in front of its quarter.
-            load_frags(nx, 0, fa[0], fb[0]);
+            // between the MFMAs, an equal share after each row of MFMA blocks, so that the matrix pipe stays
+            // fed while they issue; the pins keep each row of MFMAs in front of its share.
+            load_frags(ni_tag, nx, 0, fa[0], fb[0]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < NI; ++i) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
                     pin_one(acc[i][j]);
                 }
-                issue_part(it + kStages, it & (kStages - 1), i * (CPW / 2), (i + 1) * (CPW / 2));
-                if (i < 3) pin_one(acc[i + 1][0]);  // the next row's MFMAs read this value: they stay behind the DMA
+                issue_part(it + kStages, it & (kStages - 1), i * kDeal, (i + 1) * kDeal);
+                if (i < NI - 1) pin_one(acc[i + 1][0]);  // the next row's MFMAs read this value: they stay behind the DMA
             }
         }
         // ---- the last (up to four) stages: nothing left to issue for this tile ----
         for (; it < total; ++it) {
             const char* st = smem + (it & (kStages - 1)) * kStageBytes;
             const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
-            load_frags(st, 1, fa[1], fb[1]);
-            mma(fa[0], fb[0]);
+            load_frags(ni_tag, st, 1, fa[1], fb[1]);
+            mma(ni_tag, fa[0], fb[0]);
             interleave_mfma_dsread<kPairs>();
             const int rem = total - 1 - it;  // stages after this one, all issued already
-            pin_acc();
+            pin_acc(ni_tag);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             wait_loads(rem - 1);
             __syncthreads();
-            if (rem > 0) load_frags(nx, 0, fa[0], fb[0]);
-            mma(fa[1], fb[1]);
+            if (rem > 0) load_frags(ni_tag, nx, 0, fa[0], fb[0]);
+            mma(ni_tag, fa[1], fb[1]);
             interleave_mfma_dsread<kPairs>();
+        }
+    };
+    for (;;) {
+        const int total = t.nk * g.nseg;
+        zero_acc();
+        if constexpr (!RAGK && kWaves == 8) {
+            if (t.half) run_tile(IntTag<2>{}, total);
+            else run_tile(IntTag<4>{}, total);
+        } else {
+            run_tile(IntTag<4>{}, total);
         }
         // ---- next tile: its first stages are requested before this tile's epilogue ----
         // (every DMA load of this tile has landed and every wavefront is past the last barrier, after
