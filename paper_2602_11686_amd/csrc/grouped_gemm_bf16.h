@@ -57,7 +57,10 @@ constexpr int CPW = 16 / kWaves;           // 1 KB DMA chunks per wavefront per 
 #define MOE_VM2 8
 #define MOE_VM3 12
 #endif
-constexpr int kGemmLds = kStages * kStageBytes + 2 * (MOE_MAX_EXPERTS + 1) * 4 + 8;  // ring + expert table
+constexpr int kGemmLds = kStages * kStageBytes + 2 * (MOE_MAX_EXPERTS + 1) * 4 + 16;  // ring + expert table + 2 draw slots
+// Tile queues (GArgs::sched): one counter per XCD, kSchedStride words apart, all zero when the kernel starts.
+constexpr int kSchedStride = 32;
+constexpr int kSchedWords = 8 * kSchedStride;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4v __attribute__((ext_vector_type(4)));
@@ -137,10 +140,18 @@ struct TileDesc {
     bool half;  // ragged M: at most TM/2 live rows (the tail of an expert): computed as a 128 x 256 tile
 };
 
-// The kernel is persistent: one workgroup per CU walks the tiles  logical_tile(blockIdx.x + r *
-// gridDim.x), r = 0, 1, ...  Inside a tile the DMA loads run four k-stages ahead of the MFMAs; the
-// first stages of the next tile are requested before the current tile's epilogue, so they arrive
-// while the epilogue runs (no workgroup relaunch, no cold prologue per tile).
+// The kernel is persistent: one workgroup per CU.  Inside a tile the DMA loads run four k-stages ahead of
+// the MFMAs; the first stages of the next tile are requested before the current tile's epilogue, so they
+// arrive while the epilogue runs (no workgroup relaunch, no cold prologue per tile).
+//
+// Which tiles a workgroup runs.  Without GArgs::sched: logical_tile(blockIdx.x + r * gridDim.x), r = 0, 1, ...
+// With it: the logical tile order is cut into blocks of 32, block b belongs to the queue of XCD b % 8, and
+// the 32 workgroups of an XCD draw from their queue with an atomic counter (draw c of queue x is tile
+// ((c / 32) * 8 + x) * 32 + c % 32), then from the queues of the other XCDs once theirs is empty.  Tiles
+// differ in cost (128-row tails, experts of different row counts in wgrad), so drawing evens out the
+// finish times, while an XCD still works on one block of neighbouring tiles at a time.  The draw for the
+// next tile is made when a tile starts (one lane; its latency hides behind the main loop), reaches LDS
+// before the last barrier of the main loop and is read by all wavefronts after it.
 template <int AT, int BT, bool DUAL, int EPI, bool RAGK>
 __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     static_assert(RAGK ? (AT == 1 && BT == 0) : (AT == 0), "operand forms");
@@ -183,10 +194,50 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     }
     __syncthreads();
     const int total_tiles = t_pref[g.E];
-
-    auto decode = [&](int round) -> TileDesc {
+    // ---- tile queues ----
+    int* s_draw = reinterpret_cast<int*>(t_pref + MOE_MAX_EXPERTS + 1);  // [0]: synchronous draws, [1]: the draw made ahead
+    const bool dyn = g.sched != nullptr;
+    const int xcd = blockIdx.x & 7;
+    int qx = 0;  // queues exhausted so far; the current one is that of XCD (xcd + qx) % 8
+    auto queue_counter = [&]() { return g.sched + ((xcd + qx) & 7) * kSchedStride; };
+    auto tile_of_draw = [&](int c) { return (((c >> 5) * 8 + ((xcd + qx) & 7)) << 5) + (c & 31); };
+    // A draw that every wavefront waits for (the first tile, and the end phase when a queue has run dry);
+    // returns a tile index < total_tiles, or total_tiles when all eight queues are empty.  With `probe` the
+    // eight counters are read first (one round trip) and the queues already empty are skipped without
+    // drawing from them: a workgroup whose queue has run dry near the end of the kernel leaves after one
+    // round trip, not eight.
+    auto draw_now = [&](bool probe) -> int {
+        for (;;) {
+            if (probe) {
+                if (threadIdx.x < 64) {
+                    bool live = false;
+                    if (threadIdx.x < 8 && (int)threadIdx.x >= qx) {
+                        const int x = (xcd + threadIdx.x) & 7;
+                        const int c = (int)__hip_atomic_load(g.sched + x * kSchedStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const int L = (((c >> 5) * 8 + x) << 5) + (c & 31);
+                        live = c >= 0 && L >= 0 && L < total_tiles;
+                    }
+                    const uint64_t m = __ballot(live);
+                    if (threadIdx.x == 0) s_draw[0] = m ? __builtin_ctzll(m) : 8;
+                }
+                __syncthreads();
+                qx = s_draw[0];
+                __syncthreads();
+            }
+            if (qx >= 8) return total_tiles;
+            if (threadIdx.x == 0)
+                s_draw[0] = (int)__hip_atomic_fetch_add(queue_counter(), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const int c = s_draw[0];
+            __syncthreads();
+            const int L = tile_of_draw(c);
+            if (c >= 0 && L >= 0 && L < total_tiles) return L;
+            ++qx;
+            probe = true;
+        }
+    };
+    auto decode = [&](int L) -> TileDesc {
         TileDesc t;
-        const int L = logical_tile(blockIdx.x + round * gridDim.x);
         t.valid = L < total_tiles;
         t.e = 0; t.m0 = 0; t.m_lim = 0; t.n0 = 0; t.kbeg = 0; t.kend = 0; t.nk = 0;
         t.half = false;
@@ -678,20 +729,22 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
     int round = 0;
-    TileDesc t = decode(round);
-    while (t.valid && t.nk == 0) {  // ragged K: leading experts without rows
+    auto static_tile = [&]() { return logical_tile(blockIdx.x + round++ * gridDim.x); };
+    TileDesc t = decode(dyn ? draw_now(false) : static_tile());
+    while (t.valid && t.nk == 0) {  // ragged K: experts without rows
         epilogue_zero(t);
-        t = decode(++round);
+        t = decode(dyn ? draw_now(false) : static_tile());
     }
     if (!t.valid) return;
     di = t;
     setup_issue();
     {
         const int tot0 = t.nk * g.nseg;
-        for (int q = 0; q < kStages && q < tot0; ++q) issue(q, q);
+        for (int sq = 0; sq < kStages && sq < tot0; ++sq) issue(sq, sq);
     }
-    // The main loop of one tile; NI as in load_frags.
-    auto run_tile = [&](auto ni_tag, const int total) {
+    // The main loop of one tile; NI as in load_frags.  `ahead` (lane 0 of wavefront 0): the queue draw made
+    // when the tile started; it goes to LDS in front of the loop's last barrier.
+    auto run_tile = [&](auto ni_tag, const int total, const int ahead) {
         constexpr int NI = decltype(ni_tag)::value;
         constexpr int kReads = (AT == 0 ? NI : 2 * NI) + (BT == 1 ? NJ : 2 * NJ);
         constexpr int kPairs = kReads > NI * NJ ? kReads : NI * NJ;  // MFMA / LDS-read pairs to interleave per k-step
@@ -740,6 +793,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             pin_acc(ni_tag);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             wait_loads(rem - 1);
+            if (rem == 0 && threadIdx.x == 0) s_draw[1] = ahead;  // (rem == 0: every load of this wavefront has returned)
             __syncthreads();
             if (rem > 0) load_frags(ni_tag, nx, 0, fa[0], fb[0]);
             mma(ni_tag, fa[1], fb[1]);
@@ -749,26 +803,49 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     for (;;) {
         const int total = t.nk * g.nseg;
         zero_acc();
-        if constexpr (!RAGK && kWaves == 8) {
-            if (t.half) run_tile(IntTag<2>{}, total);
-            else run_tile(IntTag<4>{}, total);
-        } else {
-            run_tile(IntTag<4>{}, total);
+        // The draw for the next tile, as inline assembly: the compiler would wait for the returned value on
+        // the spot (it broadcasts it inside the wavefront), which stalls the first stages of the tile behind
+        // the round trip.  Like the DMA loads, this one is waited for by the loop's own vmcnt waits; the
+        // value is first read behind the vmcnt(0) of the tile's last stage.
+        int ahead = 0;
+        if (dyn && threadIdx.x == 0) {
+            const uint32_t one = 1u;
+            asm volatile("global_atomic_add %0, %1, %2, off sc0" : "=v"(ahead) : "v"(queue_counter()), "v"(one) : "memory");
         }
+        if constexpr (!RAGK && kWaves == 8) {
+            if (t.half) run_tile(IntTag<2>{}, total, ahead);
+            else run_tile(IntTag<4>{}, total, ahead);
+        } else {
+            run_tile(IntTag<4>{}, total, ahead);
+        }
+        // Nothing is outstanding here (the loop ended with vmcnt(0)); said with the builtin so that the
+        // compiler's own bookkeeping agrees and no load counts as pending in the next tile's loop.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         // ---- next tile: its first stages are requested before this tile's epilogue ----
         // (every DMA load of this tile has landed and every wavefront is past the last barrier, after
         // which nobody reads LDS any more: all four buffers are free)
-        TileDesc nt = decode(++round);
+        auto next_tile = [&](bool first) -> int {
+            if (!dyn) return static_tile();
+            if (first) {  // the draw made ahead; from an empty queue it is void, like every later draw from it
+                const int c = s_draw[1];
+                const int L = tile_of_draw(c);
+                if (c >= 0 && L >= 0 && L < total_tiles) return L;
+                ++qx;
+                return draw_now(true);
+            }
+            return draw_now(false);
+        };
+        TileDesc nt = decode(next_tile(true));
         while (nt.valid && nt.nk == 0) {
             epilogue_zero(nt);
-            nt = decode(++round);
+            nt = decode(next_tile(false));
         }
         int ntot = 0;
         if (nt.valid) {
             di = nt;
             setup_issue();
             ntot = nt.nk * g.nseg;
-            for (int q = 0; q < kStages - 1 && q < ntot; ++q) issue(q, q);
+            for (int sq = 0; sq < kStages - 1 && sq < ntot; ++sq) issue(sq, sq);
         }
         epilogue(t, smem + (kStages - 1) * kStageBytes);
         if (!nt.valid) break;
@@ -779,11 +856,13 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
 }
 
 // Experts sorted by row count, heaviest first (one workgroup; E <= 256): the wgrad tiles of a
-// heavy expert take longest, so they are started first.
+// heavy expert take longest, so they are started first.  Also clears the row of zeros and the tile queues.
 __global__ __launch_bounds__(256) void expert_order_kernel(const int32_t* __restrict__ offsets, int E,
-                                                           int32_t* __restrict__ order, uint32_t* __restrict__ zero_row) {
+                                                           int32_t* __restrict__ order, uint32_t* __restrict__ zero_row,
+                                                           uint32_t* __restrict__ sched, int sched_words) {
     const int e = threadIdx.x;
     if (e < 128) zero_row[e] = 0u;  // the 512-byte row of zeros the wgrad loads read past an expert's last row
+    for (int i = e; i < sched_words; i += 256) sched[i] = 0u;  // the tile queues of the GEMMs that follow
     if (e >= E) return;
     const int mine = offsets[e + 1] - offsets[e];
     int rank = 0;

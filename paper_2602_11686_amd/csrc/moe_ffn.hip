@@ -56,6 +56,7 @@ struct GArgs {
     const void* zero_row;  // ragged K: 512 bytes of zeros in device memory
     const int32_t* expert_of_group;  // ragged M: weights of group e are those of expert expert_of_group[e] (null: e itself)
     int n_weights;                   // experts in the weight arrays (the table's entries are clamped to it)
+    uint32_t* sched;                 // tile queues of the persistent kernel (kSchedWords words, zero at launch); null: static tile order
 };
 
 // index of the weight matrices of group e
@@ -431,12 +432,20 @@ void launch_gate_dx_gemm(const void* dl_hi, const void* dl_lo, const void* wg_pa
     kern<<<dim3(256), kThreads, kGemmLds, st>>>(g);
 }
 
+// Tile queues: the two wgrad launches draw their tiles (a tile costs as much as its expert has rows, so a
+// fixed deal leaves workgroups idle at the end: 2-4 % of the backward pass on the skewed workloads); the
+// kernels with ragged M keep the fixed order, where drawing measured no gain.
+constexpr size_t kSchedBytes = kSchedWords * sizeof(uint32_t);  // tile queues of one GEMM launch
+constexpr int kBwdLaunches = 2;
+
 size_t ffn_fwd_workspace_bytes(const moe_shape* s) {
     return align_up((size_t)s->T * s->k * s->f * el_size(s), 256);  // H
 }
 size_t ffn_bwd_workspace_bytes(const moe_shape* s) {
-    return 5 * align_up((size_t)s->T * s->k * s->f * el_size(s), 256) + 2048;  // H, dA, dB, (A, B when recomputing), expert order, a row of zeros
+    // H, dA, dB, (A, B when recomputing), expert order, a row of zeros, tile queues
+    return 5 * align_up((size_t)s->T * s->k * s->f * el_size(s), 256) + 2048 + kBwdLaunches * kSchedBytes;
 }
+
 
 }  // namespace moe
 
@@ -545,7 +554,9 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     void* dB = cv.take(rf);
     int32_t* order = static_cast<int32_t*>(cv.take(1024));
     void* zero_row = cv.take(512);
-    expert_order_kernel<<<1, 256, 0, st>>>(offsets, s->E, order, static_cast<uint32_t*>(zero_row));
+    uint32_t* sched = static_cast<uint32_t*>(cv.take(kBwdLaunches * kSchedBytes));
+    expert_order_kernel<<<1, 256, 0, st>>>(offsets, s->E, order, static_cast<uint32_t*>(zero_row), sched,
+                                           kBwdLaunches * kSchedWords);
     if (!a_save || !b_save) {  // expert-only recomputation: rebuild A and B (H is rewritten below anyway)
         void* A = cv.take(rf);
         void* B = cv.take(rf);
@@ -576,6 +587,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
         g.seg[0] = {H, dy_perm, nullptr};
         g.lda = s->f; g.ldb = s->d; g.strideC = (int64_t)s->f * s->d;
         g.C0 = dw2; g.ldc = s->d; g.order = order; g.zero_row = zero_row;
+        g.sched = sched;
         launch_gg<1, 0, false, EPI_STORE, true>(s, g, R, st);
     }
     {  // [dW1|dW3][e] = Xp_e^T * [dA_e|dB_e]
@@ -584,6 +596,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
         g.seg[0] = {x_perm, dA, dB};
         g.lda = s->d; g.ldb = s->f; g.strideC = (int64_t)s->d * s->f;
         g.C0 = dw1; g.C1 = dw3; g.ldc = s->f; g.order = order; g.zero_row = zero_row;
+        g.sched = sched + kSchedWords;
         launch_gg<1, 0, true, EPI_STORE2, true>(s, g, R, st);
     }
     return launch_status(who);
