@@ -65,6 +65,7 @@ constexpr int kSchedWords = 8 * kSchedStride;
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 typedef float f32x2v __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define LDS_AS __attribute__((address_space(3)))
 
@@ -496,8 +497,8 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
 
     // ---- epilogue of one tile.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
     // inside a 32x32 block) go through LDS, 64 rows at a time (block i of both wavefront rows), so that
-    // global memory sees 16-byte accesses along rows.  `stg` is the 32 KB ring buffer of the stage
-    // consumed last; the other three buffers hold the next tile's first stages.
+    // global memory sees 16-byte accesses along rows.  `stg` is the last 32 KB ring buffer; the bf16 epilogues
+    // also use the one in front of it, the first kPreStages buffers hold the next tile's first stages.
     auto epilogue_zero = [&](const TileDesc& t) {  // ragged K, expert without rows: exact zeros, no staging needed
         const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
         {
@@ -640,28 +641,38 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
         } else {
             // bf16 tiles: stage [64 rows][ROWB bytes] with swizzled 16-byte pieces, then 16 bytes per lane along rows.
+            // Two staging buffers (ring buffers 2 and 3; 0 and 1 hold the next tile's first stages) take the
+            // passes in turn, so one barrier per pass is enough: a wavefront that writes pass p+2 has passed the
+            // barrier of pass p+1, which every wavefront reaches only after it has read pass p.
             constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
             constexpr int PPR = ROWB / 16;  // pieces per row
-            // Two accumulators of a lane that sit in consecutive rows (r0 = 2m, r0+1) are traded with the
-            // neighbouring lane (next column): the even lane ends up with row r0, columns (c, c+1), the odd
-            // lane with row r0+1, columns (c-1, c).  One packed conversion and one 4-byte LDS write per pair.
-            // Staging swizzle: piece ^ (8*((row>>2)&1) + 4*(row&1)) keeps the four lane groups of a write
-            // (even/odd lanes, lower/upper half of the wavefront) on different banks.
-            const bool odd = (lane & 1) != 0;
-            auto stg_sw = [](int sr) { return (((sr >> 2) & 1) << 3) | ((sr & 1) << 2); };
-            auto put2 = [&](int r0, int colbase, float v0, float v1) {
-                const float send = odd ? v0 : v1;
-                const float recv = __builtin_bit_cast(
-                    float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, send), 0xB1, 0xf, 0xf, true));  // quad_perm [1,0,3,2]
-                f32x2v pr;
-                pr[0] = odd ? recv : v0;
-                pr[1] = odd ? v1 : recv;
-                const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
-                const int sr = wm * 32 + (r0 >> 2) * 8 + kg * 4 + (r0 & 3) + (odd ? 1 : 0);
-                const int col = colbase + (l32 & ~1);
-                *reinterpret_cast<bf16x2*>(stg + sr * ROWB + (((col >> 3) ^ stg_sw(sr)) << 4) + (col & 7) * 2) = pk;
+            // Four accumulators r = 4g .. 4g+3 of a lane are four consecutive rows of one column.  A 4x4
+            // transpose inside each quad of lanes (two DPP exchanges: neighbouring lanes trade single values,
+            // then lanes two apart trade packed pairs) leaves lane q of the quad with row q, columns c .. c+3:
+            // two packed conversions and one 8-byte LDS write per four values.
+            // Staging swizzle: piece ^ 4*(row & 3) puts the four rows of a quad's write 64 bytes apart in the banks.
+            const int q4 = lane & 3;
+            const bool odd = (q4 & 1) != 0, upper = (q4 >> 1) != 0;
+            auto stg_sw = [](int sr) { return (sr & 3) << 2; };
+            auto put4 = [&](char* sb, int g4, int colbase, float v0, float v1, float v2, float v3) {
+                auto swap1 = [](float x) {
+                    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));  // quad_perm [1,0,3,2]
+                };
+                const float r01 = swap1(odd ? v0 : v1), r23 = swap1(odd ? v2 : v3);
+                f32x2v a, b;
+                a[0] = odd ? r01 : v0; a[1] = odd ? v1 : r01;  // even lane: row 0, odd lane: row 1; columns (even, odd) of the pair
+                b[0] = odd ? r23 : v2; b[1] = odd ? v3 : r23;  // rows 2 and 3
+                const uint32_t p01 = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
+                const uint32_t p23 = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
+                const uint32_t got = (uint32_t)__builtin_amdgcn_mov_dpp((int)(upper ? p01 : p23), 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
+                u32x2 o;
+                o[0] = upper ? got : p01;  // lanes 0, 1: rows 0, 1 (own pair, then the pair of the lane two up)
+                o[1] = upper ? p23 : got;  // lanes 2, 3: rows 2, 3
+                const int sr = wm * 32 + g4 * 8 + kg * 4 + q4;
+                const int col = colbase + (l32 & ~3);
+                *reinterpret_cast<u32x2*>(sb + sr * ROWB + (((col >> 3) ^ stg_sw(sr)) << 4) + (col & 7) * 2) = o;
             };
-            auto flush = [&](int i, bf16_t* dst0, bf16_t* dst1, int cols0) {
+            auto flush = [&](const char* sb, int i, bf16_t* dst0, bf16_t* dst1, int cols0) {
                 __syncthreads();
                 for (int item = threadIdx.x; item < 64 * PPR; item += kThreads) {
                     const int sr = item / PPR, pc = item - sr * PPR;
@@ -672,55 +683,64 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                     const int gcol = t.n0 + col;
                     if (grow < t.m_lim && gcol < g.N)
                         *reinterpret_cast<u32x4*>(dst + cbase + (int64_t)grow * g.ldc + gcol) =
-                            *reinterpret_cast<const u32x4*>(stg + sr * ROWB + ((pc ^ stg_sw(sr)) << 4));
+                            *reinterpret_cast<const u32x4*>(sb + sr * ROWB + ((pc ^ stg_sw(sr)) << 4));
                 }
-                __syncthreads();
             };
+            int pn = 0;  // passes so far
+            auto next_buf = [&]() { return stg - ((pn++ & 1) ? 0 : kStageBytes); };  // ring buffers 2, 3, 2, ...
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (i >= ni) break;
                 if constexpr (EPI == EPI_SWIGLU) {
                     for (int pass = 0; pass < (g.S0 ? 3 : 1); ++pass) {
+                        char* sb = next_buf();
 #pragma unroll
                         for (int j = 0; j < NJ / 2; ++j)
 #pragma unroll
-                            for (int r = 0; r < 16; r += 2) {
-                                float v[2];
+                            for (int g4 = 0; g4 < 4; ++g4) {
+                                float v[4];
 #pragma unroll
-                                for (int z = 0; z < 2; ++z) {
-                                    const float a = acc[i][j][r + z], b = acc[i][j + NJ / 2][r + z];
+                                for (int z = 0; z < 4; ++z) {
+                                    const float a = acc[i][j][4 * g4 + z], b = acc[i][j + NJ / 2][4 * g4 + z];
                                     v[z] = pass == 0 ? silu_f(a) * b : pass == 1 ? a : b;
                                 }
-                                put2(r, wn * (NJ / 2) * 32 + j * 32, v[0], v[1]);
+                                put4(sb, g4, wn * (NJ / 2) * 32 + j * 32, v[0], v[1], v[2], v[3]);
                             }
                         bf16_t* dst = pass == 0 ? static_cast<bf16_t*>(g.C0)
                                                 : const_cast<bf16_t*>(static_cast<const bf16_t*>(pass == 1 ? g.S0 : g.S1));
-                        flush(i, dst, nullptr, 0);
+                        flush(sb, i, dst, nullptr, 0);
                     }
                 } else if constexpr (DUAL) {  // EPI_STORE2: first 128 columns -> C0, second 128 -> C1
+                    char* sb = next_buf();
 #pragma unroll
                     for (int j = 0; j < NJ / 2; ++j)
 #pragma unroll
-                        for (int r = 0; r < 16; r += 2) {
-                            put2(r, wn * (NJ / 2) * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1]);
-                            put2(r, 128 + wn * (NJ / 2) * 32 + j * 32, acc[i][j + NJ / 2][r], acc[i][j + NJ / 2][r + 1]);
+                        for (int g4 = 0; g4 < 4; ++g4) {
+                            const int r = 4 * g4;
+                            put4(sb, g4, wn * (NJ / 2) * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1], acc[i][j][r + 2], acc[i][j][r + 3]);
+                            put4(sb, g4, 128 + wn * (NJ / 2) * 32 + j * 32, acc[i][j + NJ / 2][r], acc[i][j + NJ / 2][r + 1],
+                                 acc[i][j + NJ / 2][r + 2], acc[i][j + NJ / 2][r + 3]);
                         }
-                    flush(i, static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
+                    flush(sb, i, static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
                 } else {  // EPI_STORE
+                    char* sb = next_buf();
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                        for (int r = 0; r < 16; r += 2)
-                            put2(r, wn * NJ * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1]);
-                    flush(i, static_cast<bf16_t*>(g.C0), nullptr, 0);
+                        for (int g4 = 0; g4 < 4; ++g4) {
+                            const int r = 4 * g4;
+                            put4(sb, g4, wn * NJ * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1], acc[i][j][r + 2], acc[i][j][r + 3]);
+                        }
+                    flush(sb, i, static_cast<bf16_t*>(g.C0), nullptr, 0);
                 }
             }
+            __syncthreads();  // the last two passes have been read: both staging buffers may take the next tile's stages
         }
     };
 
     // ================= the tiles of this workgroup =================
-    // Per tile: stages 0..3 are in flight when its loop starts (stages 0..2 were issued before the
-    // previous tile's epilogue, stage 3 after it); the barrier in the middle of iteration `it`
+    // Per tile: stages 0..3 are in flight when its loop starts (the first kPreStages of them were issued
+    // before the previous tile's epilogue, the others after it); the barrier in the middle of iteration `it`
     // publishes stage it+1 and frees the buffer of stage it, into which stage it+4 is issued at once.
     bf16x8 fa[2][4], fb[2][NJ];
     auto wait_loads = [&](int stages_allowed) {  // at most that many of the youngest stage loads may be pending
@@ -800,6 +820,8 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             interleave_mfma_dsread<kPairs>();
         }
     };
+    // Stages of the next tile requested before this tile's epilogue; the epilogue stages through the other ring buffers.
+    constexpr int kPreStages = (EPI == EPI_STORE || EPI == EPI_STORE2 || EPI == EPI_SWIGLU) ? kStages - 2 : kStages - 1;
     for (;;) {
         const int total = t.nk * g.nseg;
         zero_acc();
@@ -845,11 +867,11 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             di = nt;
             setup_issue();
             ntot = nt.nk * g.nseg;
-            for (int sq = 0; sq < kStages - 1 && sq < ntot; ++sq) issue(sq, sq);
+            for (int sq = 0; sq < kPreStages && sq < ntot; ++sq) issue(sq, sq);
         }
         epilogue(t, smem + (kStages - 1) * kStageBytes);
         if (!nt.valid) break;
-        if (ntot >= kStages) issue(kStages - 1, kStages - 1);
+        for (int sq = kPreStages; sq < kStages && sq < ntot; ++sq) issue(sq, sq);
         t = nt;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
