@@ -69,6 +69,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define LDS_AS __attribute__((address_space(3)))
 
+
 // Scheduling pattern for one k-step: MFMA, LDS read, MFMA, LDS read, ... then a fence.
 template <int N>
 __device__ __forceinline__ void interleave_mfma_dsread() {
@@ -607,7 +608,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                             for (int q = 0; q < 4; ++q) {
                                 const float lo = __uint_as_float(old[q] << 16) + dh[2 * q];
                                 const float hi = __uint_as_float(old[q] & 0xFFFF0000u) + dh[2 * q + 1];
-                                o[q] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+                                o[q] = pack_bf16x2(lo, hi);
                             }
                             if (live[u]) *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = o;
                         } else {
@@ -620,14 +621,16 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                                 for (int z = 0; z < 2; ++z) {
                                     const float A = __uint_as_float(z ? (av[q] & 0xFFFF0000u) : (av[q] << 16));
                                     const float B = __uint_as_float(z ? (bv[q] & 0xFFFF0000u) : (bv[q] << 16));
-                                    const float sA = silu_f(A);
+                                    const float sg = sigmoid_f(A);             // one exp and one reciprocal per element
+                                    const float sA = A * sg;                   // silu(A)
+                                    const float gr = sg + sA * (1.0f - sg);    // silu'(A) = s (1 + A (1 - s))
                                     hh[z] = sA * B;
-                                    da[z] = dh[2 * q + z] * B * silu_grad_f(A);
+                                    da[z] = dh[2 * q + z] * B * gr;
                                     db[z] = dh[2 * q + z] * sA;
                                 }
-                                oh[q] = (uint32_t)f32_to_bf16(hh[0]) | ((uint32_t)f32_to_bf16(hh[1]) << 16);
-                                oa[q] = (uint32_t)f32_to_bf16(da[0]) | ((uint32_t)f32_to_bf16(da[1]) << 16);
-                                ob[q] = (uint32_t)f32_to_bf16(db[0]) | ((uint32_t)f32_to_bf16(db[1]) << 16);
+                                oh[q] = pack_bf16x2(hh[0], hh[1]);
+                                oa[q] = pack_bf16x2(da[0], da[1]);
+                                ob[q] = pack_bf16x2(db[0], db[1]);
                             }
                             if (live[u]) {
                                 *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = oh;

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void fsep_reshard_kernel(const fu32x4* __restr
         if constexpr (sizeof(T) == 2) {
 #pragma unroll
             for (int z = 0; z < 4; ++z)
-                out[z] = (uint32_t)f32_to_bf16(acc[2 * z]) | ((uint32_t)f32_to_bf16(acc[2 * z + 1]) << 16);
+                out[z] = pack_bf16x2(acc[2 * z], acc[2 * z + 1]);
         } else {
 #pragma unroll
             for (int z = 0; z < 4; ++z) out[z] = __float_as_uint(acc[z]);

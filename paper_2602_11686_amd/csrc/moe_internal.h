@@ -62,6 +62,17 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float x) {
     return (bf16_t)(u >> 16);
 }
 
+// two fp32 values -> two bf16 in one dword (low half first), round to nearest even, with the packed conversion
+// instruction of gfx950 (inputs are finite by contract)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    f32x2_t v;
+    v[0] = lo;
+    v[1] = hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 template <class T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float* p) { return *p; }
