@@ -195,7 +195,17 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         if (lane == 63) t_pref[MOE_MAX_EXPERTS] = run;
     }
     __syncthreads();
-    const int total_tiles = t_pref[g.E];
+    // Ragged M in the fixed tile order: when the last round of tiles fills at most half of the workgroups, its
+    // tiles are cut into their upper and lower 128 rows (logical tiles split_from + 2i and + 2i + 1), so that
+    // the round costs a 128-row tile's time instead of a full one's.
+    int total_tiles = t_pref[g.E], split_from = total_tiles;
+    if constexpr (!RAGK && kWaves == 8) {
+        const int left = total_tiles % (int)gridDim.x;
+        if (g.sched == nullptr && left > 0 && 2 * left <= (int)gridDim.x) {
+            split_from = total_tiles - left;
+            total_tiles += left;
+        }
+    }
     // ---- tile queues ----
     int* s_draw = reinterpret_cast<int*>(t_pref + MOE_MAX_EXPERTS + 1);  // [0]: synchronous draws, [1]: the draw made ahead
     const bool dyn = g.sched != nullptr;
@@ -244,6 +254,11 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         t.e = 0; t.m0 = 0; t.m_lim = 0; t.n0 = 0; t.kbeg = 0; t.kend = 0; t.nk = 0;
         t.half = false;
         if (!t.valid) return t;
+        int part = -1;  // which half of a split tile
+        if (L >= split_from) {
+            part = (L - split_from) & 1;
+            L = split_from + ((L - split_from) >> 1);
+        }
         int m, nt;
         if constexpr (RAGK) {
             const int per = m_tiles_k * n_tiles;
@@ -269,9 +284,14 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             t.m0 = b + m * TM;
             t.m_lim = en;
             t.kend = g.K;
+            if (part >= 0) {  // rows [m0 + 128*part, m0 + 128*part + 128) of the tile, as far as the expert reaches
+                t.m0 += part * (TM / 2);
+                t.m_lim = min(en, t.m0 + TM / 2);
+            }
         }
         t.n0 = nt * n_out;
         t.nk = (t.kend - t.kbeg + TK - 1) / TK;  // exact when M is ragged (K % 32 == 0)
+        if (!RAGK && t.m0 >= t.m_lim) t.nk = 0;   // the lower half of a tile of at most 128 rows: nothing to do
         t.e = __builtin_amdgcn_readfirstlane(t.e);
         t.m0 = __builtin_amdgcn_readfirstlane(t.m0);
         t.m_lim = __builtin_amdgcn_readfirstlane(t.m_lim);
@@ -754,8 +774,8 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     int round = 0;
     auto static_tile = [&]() { return logical_tile(blockIdx.x + round++ * gridDim.x); };
     TileDesc t = decode(dyn ? draw_now(false) : static_tile());
-    while (t.valid && t.nk == 0) {  // ragged K: experts without rows
-        epilogue_zero(t);
+    while (t.valid && t.nk == 0) {  // ragged K: experts without rows; ragged M: empty halves of split tiles
+        if constexpr (RAGK) epilogue_zero(t);
         t = decode(dyn ? draw_now(false) : static_tile());
     }
     if (!t.valid) return;
@@ -862,7 +882,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         };
         TileDesc nt = decode(next_tile(true));
         while (nt.valid && nt.nk == 0) {
-            epilogue_zero(nt);
+            if constexpr (RAGK) epilogue_zero(nt);
             nt = decode(next_tile(false));
         }
         int ntot = 0;
