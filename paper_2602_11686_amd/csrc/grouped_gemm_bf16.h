@@ -670,23 +670,24 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
             constexpr int PPR = ROWB / 16;  // pieces per row
             // Four accumulators r = 4g .. 4g+3 of a lane are four consecutive rows of one column.  A 4x4
-            // transpose inside each quad of lanes (two DPP exchanges: neighbouring lanes trade single values,
-            // then lanes two apart trade packed pairs) leaves lane q of the quad with row q, columns c .. c+3:
-            // two packed conversions and one 8-byte LDS write per four values.
+            // transpose inside each quad of lanes (two packed conversions, then two exchanges of packed pairs over
+            // DPP: with the neighbouring lane, merged by a byte permute, and with the lane two apart) leaves lane q
+            // of the quad with row q, columns c .. c+3: one 8-byte LDS write per four values.
             // Staging swizzle: piece ^ 4*(row & 3) puts the four rows of a quad's write 64 bytes apart in the banks.
             const int q4 = lane & 3;
             const bool odd = (q4 & 1) != 0, upper = (q4 >> 1) != 0;
             auto stg_sw = [](int sr) { return (sr & 3) << 2; };
+            // byte selector of the first exchange (v_perm_b32 over {own pair, neighbour's pair}): the even lane of
+            // a pair keeps the low halves (row 0 resp. 2: its own column, then the neighbour's), the odd lane the
+            // high halves (row 1 resp. 3: the neighbour's column, then its own)
+            const uint32_t sel1 = odd ? 0x07060302u : 0x01000504u;
             auto put4 = [&](char* sb, int g4, int colbase, float v0, float v1, float v2, float v3) {
-                auto swap1 = [](float x) {
-                    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));  // quad_perm [1,0,3,2]
+                auto swap1 = [](uint32_t x) {
+                    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xf, 0xf, true);  // quad_perm [1,0,3,2]
                 };
-                const float r01 = swap1(odd ? v0 : v1), r23 = swap1(odd ? v2 : v3);
-                f32x2v a, b;
-                a[0] = odd ? r01 : v0; a[1] = odd ? v1 : r01;  // even lane: row 0, odd lane: row 1; columns (even, odd) of the pair
-                b[0] = odd ? r23 : v2; b[1] = odd ? v3 : r23;  // rows 2 and 3
-                const uint32_t p01 = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
-                const uint32_t p23 = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
+                const uint32_t c01 = pack_bf16x2(v0, v1), c23 = pack_bf16x2(v2, v3);  // this lane's column, rows (0,1), (2,3)
+                const uint32_t p01 = __builtin_amdgcn_perm(c01, swap1(c01), sel1);    // row 0 | 1, columns (even, odd) of the pair
+                const uint32_t p23 = __builtin_amdgcn_perm(c23, swap1(c23), sel1);    // row 2 | 3
                 const uint32_t got = (uint32_t)__builtin_amdgcn_mov_dpp((int)(upper ? p01 : p23), 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
                 u32x2 o;
                 o[0] = upper ? got : p01;  // lanes 0, 1: rows 0, 1 (own pair, then the pair of the lane two up)
