@@ -7,18 +7,25 @@
 // copy work plus a small integer sort, so the kernels move rows as 16-byte
 // vectors, read each token row once, and keep all counts on the device.
 //
-// Stable counting sort of the R = T*k pairs, in three small kernels:
+// Stable counting sort of the R = T*k pairs:
 //   1. per-chunk histograms (one wavefront owns CHUNK consecutive pairs),
-//   2. one workgroup turns them into per-chunk starting rows (exclusive scan
-//      down the chunks for every expert, then across experts),
+//   2. per-chunk starting rows (exclusive scan down the chunks for every expert,
+//      then across experts),
 //   3. each wavefront walks its chunk in order, 64 pairs at a time: lanes with
 //      the same expert are found with 8 ballots over the bits of the expert id,
 //      the lane's rank is the running count of its expert plus the number of
 //      lower lanes in its group.
-// A fourth kernel copies the rows: one pass over x, k row writes per token.
+// moe_permute runs 1 as one kernel and 2 + 3 as a second one, in which every
+// workgroup redoes the scan for its own chunks; moe_permute_lite keeps 2 as a
+// one-workgroup kernel of its own, because it also checks and expands the
+// replica table there.  A last kernel copies the rows: one pass over x, k row
+// writes per token.
 #include "moe_internal.h"
 
 namespace moe {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // pairs per wavefront in the sort: 128, doubled until there are at most 256 chunks (the scan walks the
 // chunks of an expert one after the other; short chunks keep the histogram and rank kernels parallel)
@@ -58,7 +65,7 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __rest
         for (int e = lane; e < E; e += 64) chunk_hist[(size_t)chunk * E + e] = h[e];
 }
 
-// ---- 2. scan: chunk_base[c][e] = first row of chunk c for expert e ---------------------
+// ---- 2. scan helpers (lite routing): chunk_base[c][e] = rank of the first pair of chunk c inside expert e ----
 // 256 threads = P parts x E experts (P = 256 / E): part p of expert e owns a contiguous range of
 // chunks, sums it, and after the parts' sums and the experts' offsets are known writes the running
 // base of every chunk of its range.  Input and output are different arrays, so the loads of the
@@ -128,54 +135,102 @@ __device__ __forceinline__ void scan_range_write(const int32_t* __restrict__ chu
     }
 }
 
-__global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __restrict__ chunk_hist,
-                                                           int32_t* __restrict__ chunk_base, int nchunks, int E,
-                                                           int32_t* __restrict__ counts,
-                                                           int32_t* __restrict__ offsets) {
-    __shared__ int32_t psum[256];                    // [part][expert]
-    __shared__ int32_t off[MOE_MAX_EXPERTS + 1];
-    const ScanParts sp = scan_parts(nchunks, E);
-    psum[threadIdx.x] = sp.part < sp.P ? scan_range_sum(chunk_hist, E, sp) : 0;
-    __syncthreads();
-    int32_t before = 0, total = 0;                   // this expert: sum of the earlier parts, sum of all parts
-    if (sp.part < sp.P)
-        for (int p = 0; p < sp.P; ++p) {
-            const int32_t v = psum[p * E + sp.e];
-            if (p < sp.part) before += v;
-            total += v;
+// ---- 2 + 3 in one launch --------------------------------------------------------------------
+// Every workgroup redoes the part of the scan it needs instead of waiting for a one-workgroup scan kernel:
+// 1024 threads = P parts x E experts sum the chunk histograms (all chunks: the experts' totals; the chunks
+// before this workgroup's: the rows already taken), one wavefront scans the totals across the experts, and
+// the first four wavefronts then rank one chunk each as in step 3.  The histograms are read by every
+// workgroup (nchunks * E * 4 bytes, from L2), which is cheaper than a launch that all of them wait for.
+constexpr int kRankScanThreads = 1024;
+__global__ __launch_bounds__(kRankScanThreads) void permute_rank_scan_kernel(
+    const int32_t* __restrict__ ids, int R, int E, int kChunk, const int32_t* __restrict__ chunk_hist, int nchunks,
+    int32_t* __restrict__ counts, int32_t* __restrict__ offsets, int32_t* __restrict__ row_of_pair,
+    int32_t* __restrict__ pair_of_row) {
+    __shared__ int32_t ps_all[kRankScanThreads], ps_before[kRankScanThreads];  // [part][expert]
+    __shared__ int32_t e_total[MOE_MAX_EXPERTS], e_before[MOE_MAX_EXPERTS], e_off[MOE_MAX_EXPERTS + 1];
+    __shared__ int32_t lds_next[kWavesPerBlock * MOE_MAX_EXPERTS];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c_first = blockIdx.x * kWavesPerBlock;
+    int P = kRankScanThreads / E;  // E <= 256: at least 4 parts
+    if (P > 32) P = 32;
+    {
+        const int e = tid % E, part = tid / E;
+        int32_t all = 0, before = 0;
+        if (part < P) {
+            const int len = (nchunks + P - 1) / P;
+            const int cb = min(part * len, nchunks), ce = min(cb + len, nchunks);
+            int c = cb;
+            for (; c + 16 <= ce; c += 16) {
+                int32_t v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = chunk_hist[(size_t)(c + u) * E + e];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    all += v[u];
+                    before += (c + u < c_first) ? v[u] : 0;
+                }
+            }
+            for (; c < ce; ++c) {
+                const int32_t v = chunk_hist[(size_t)c * E + e];
+                all += v;
+                before += (c < c_first) ? v : 0;
+            }
+            ps_all[part * E + e] = all;
+            ps_before[part * E + e] = before;
         }
-    __syncthreads();
-    if (sp.part == 0) {
-        psum[sp.e] = total;                           // reuse: per-expert counts
-        counts[sp.e] = total;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int32_t run = 0;
-        for (int i = 0; i < E; ++i) {
-            off[i] = run;
-            run += psum[i];
+    if (tid < E) {
+        int32_t all = 0, before = 0;
+        for (int p = 0; p < P; ++p) {
+            all += ps_all[p * E + tid];
+            before += ps_before[p * E + tid];
         }
-        off[E] = run;
+        e_total[tid] = all;
+        e_before[tid] = before;
     }
     __syncthreads();
-    if (sp.part == 0) offsets[sp.e] = off[sp.e];
-    if (threadIdx.x == 0) offsets[E] = off[E];
-    if (sp.part < sp.P) scan_range_write(chunk_hist, chunk_base, E, sp, off[sp.e] + before);
-}
-
-// ---- 3. stable rank of every pair ---------------------------------------------------
-__global__ __launch_bounds__(256) void permute_rank_kernel(const int32_t* __restrict__ ids, int R, int E, int kChunk,
-                                                           const int32_t* __restrict__ chunk_base,
-                                                           int32_t* __restrict__ row_of_pair,
-                                                           int32_t* __restrict__ pair_of_row) {
-    extern __shared__ int32_t lds_next[];  // [kWavesPerBlock][E] next free row per expert
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int chunk = blockIdx.x * kWavesPerBlock + wave;
+    if (wave == 0) {  // exclusive scan of the totals: 4 experts per lane, then across the lanes
+        int32_t c[4], sum = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = lane * 4 + u;
+            c[u] = e < E ? e_total[e] : 0;
+            sum += c[u];
+        }
+        int32_t incl = sum;
+#pragma unroll
+        for (int dlt = 1; dlt < 64; dlt <<= 1) {
+            const int32_t o = __shfl_up(incl, dlt, 64);
+            if (lane >= dlt) incl += o;
+        }
+        int32_t run = incl - sum;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = lane * 4 + u;
+            if (e <= E) e_off[e] = run;
+            run += c[u];
+        }
+        if (lane == 63 && E == MOE_MAX_EXPERTS) e_off[MOE_MAX_EXPERTS] = run;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        if (tid < E) {
+            counts[tid] = e_total[tid];
+            offsets[tid] = e_off[tid];
+        }
+        if (tid == 0) offsets[E] = e_off[E];
+    }
+    if (wave >= kWavesPerBlock) return;  // whole wavefronts leave; no workgroup barrier below
+    const int chunk = c_first + wave;
     const int p0 = chunk * kChunk;
-    if (p0 >= R) return;  // whole wavefront leaves together; no barrier below
+    if (p0 >= R) return;
     int32_t* next = lds_next + wave * E;
-    for (int e = lane; e < E; e += 64) next[e] = chunk_base[(size_t)chunk * E + e];
+    for (int e = lane; e < E; e += 64) {
+        int32_t b = e_off[e] + e_before[e];
+        for (int j = 0; j < wave; ++j) b += chunk_hist[(size_t)(c_first + j) * E + e];
+        next[e] = b;
+    }
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
     for (int i = 0; i < kChunk; i += 64) {
         const int p = p0 + i + lane;
@@ -194,8 +249,6 @@ __global__ __launch_bounds__(256) void permute_rank_kernel(const int32_t* __rest
             row_of_pair[p] = row;
             pair_of_row[row] = p;
         }
-        // the highest lane of each group advances the expert's counter; the wave
-        // executes in lockstep, so all reads above precede these writes
         __builtin_amdgcn_wave_barrier();
         if (live && (same >> lane) == 1ull) next[e] += __popcll(same);
         __builtin_amdgcn_wave_barrier();
@@ -383,8 +436,8 @@ __global__ __launch_bounds__(256) void permute_rank_lite_kernel(const int32_t* _
 }
 
 // ---- 4. row scatter: x[t] -> x_perm[row_of_pair[t*k+s]] for s < k ----------------------
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+template <int KT>  // KT > 0: k at compile time (the k row indices are requested together); 0: any k
 __global__ __launch_bounds__(256) void permute_scatter_rows_kernel(const u32x4* __restrict__ x,
                                                                    const int32_t* __restrict__ row_of_pair,
                                                                    u32x4* __restrict__ x_perm, int T, int k,
@@ -395,9 +448,17 @@ __global__ __launch_bounds__(256) void permute_scatter_rows_kernel(const u32x4* 
         const int t = (int)(i / vecs_per_row);
         const int v = (int)(i - (int64_t)t * vecs_per_row);
         const u32x4 val = __builtin_nontemporal_load(&x[i]);
-        for (int s = 0; s < k; ++s) {
-            const int row = row_of_pair[(size_t)t * k + s];
-            __builtin_nontemporal_store(val, &x_perm[(size_t)row * vecs_per_row + v]);
+        if constexpr (KT > 0) {
+            int rows[KT];
+#pragma unroll
+            for (int s = 0; s < KT; ++s) rows[s] = row_of_pair[(size_t)t * KT + s];
+#pragma unroll
+            for (int s = 0; s < KT; ++s) __builtin_nontemporal_store(val, &x_perm[(size_t)rows[s] * vecs_per_row + v]);
+        } else {
+            for (int s = 0; s < k; ++s) {
+                const int row = row_of_pair[(size_t)t * k + s];
+                __builtin_nontemporal_store(val, &x_perm[(size_t)row * vecs_per_row + v]);
+            }
         }
     }
 }
@@ -407,35 +468,55 @@ template <class T, int VEC>
 struct VecIO;
 template <>
 struct VecIO<bf16_t, 8> {
+    template <bool NT = false>
     static __device__ __forceinline__ void load(const void* p, float (&v)[8]) {
-        const uint4 u = *reinterpret_cast<const uint4*>(p);
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+        u32x4 u;
+        if constexpr (NT) u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        else u = *reinterpret_cast<const u32x4*>(p);
+        const uint32_t w[4] = {u[0], u[1], u[2], u[3]};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             v[2 * i] = __uint_as_float(w[i] << 16);
             v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
         }
     }
+    template <bool NT = false>
     static __device__ __forceinline__ void store(void* p, const float (&v)[8]) {
         uint32_t w[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
-        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+        u32x4 o;
+        o[0] = w[0]; o[1] = w[1]; o[2] = w[2]; o[3] = w[3];
+        if constexpr (NT) __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(p));
+        else *reinterpret_cast<u32x4*>(p) = o;
     }
 };
 template <>
 struct VecIO<float, 4> {
+    template <bool NT = false>
     static __device__ __forceinline__ void load(const void* p, float (&v)[4]) {
-        const float4 u = *reinterpret_cast<const float4*>(p);
-        v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+        f32x4 u;
+        if constexpr (NT) u = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+        else u = *reinterpret_cast<const f32x4*>(p);
+        v[0] = u[0]; v[1] = u[1]; v[2] = u[2]; v[3] = u[3];
     }
+    template <bool NT = false>
     static __device__ __forceinline__ void store(void* p, const float (&v)[4]) {
-        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        f32x4 u;
+        u[0] = v[0]; u[1] = v[1]; u[2] = v[2]; u[3] = v[3];
+        if constexpr (NT) __builtin_nontemporal_store(u, reinterpret_cast<f32x4*>(p));
+        else *reinterpret_cast<f32x4*>(p) = u;
     }
 };
 
-template <class T, int VEC>
+// KT > 0: k is known at compile time, so the k row indices, then the k row pieces, are all requested before
+// the first of them is used (a gather is bound by how many loads are in flight, not by arithmetic).
+// KT == 0: any k, one row after the other.  The sum runs over s = 0 .. k-1 in this order either way.
+// The rows of y_perm are read once and are loaded non-temporally, so that they do not push the output (which
+// the next kernel reads) out of the caches; the same holds for y_perm in the backward kernel below.  Measured:
+// non-temporal stores of the outputs make the kernels that follow slower.
+template <class T, int VEC, int KT>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_perm,
                                                       const int32_t* __restrict__ row_of_pair,
                                                       const float* __restrict__ w, T* __restrict__ y, int Tn,
@@ -449,20 +530,41 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
         float acc[VEC];
 #pragma unroll
         for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
-        for (int s = 0; s < k; ++s) {
-            const int row = row_of_pair[(size_t)t * k + s];
-            const float ws = w ? w[(size_t)t * k + s] : 1.0f;
-            float val[VEC];
-            VecIO<T, VEC>::load(y_perm + (size_t)row * d + (size_t)v * VEC, val);
+        if constexpr (KT > 0) {
+            int rows[KT];
+            float ws[KT];
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[j] += ws * val[j];
+            for (int s = 0; s < KT; ++s) {
+                rows[s] = row_of_pair[(size_t)t * KT + s];
+                ws[s] = w ? w[(size_t)t * KT + s] : 1.0f;
+            }
+            float val[KT][VEC];
+#pragma unroll
+            for (int s = 0; s < KT; ++s) VecIO<T, VEC>::template load<true>(y_perm + (size_t)rows[s] * d + (size_t)v * VEC, val[s]);
+#pragma unroll
+            for (int s = 0; s < KT; ++s)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] += ws[s] * val[s][j];
+        } else {
+            for (int s = 0; s < k; ++s) {
+                const int row = row_of_pair[(size_t)t * k + s];
+                const float ws = w ? w[(size_t)t * k + s] : 1.0f;
+                float val[VEC];
+                VecIO<T, VEC>::template load<true>(y_perm + (size_t)row * d + (size_t)v * VEC, val);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] += ws * val[j];
+            }
         }
         VecIO<T, VEC>::store(y + (size_t)t * d + (size_t)v * VEC, acc);
     }
 }
 
 // ---- combine backward: one wavefront per token -----------------------------------
-template <class T, int VEC>
+// dy_perm[row(t,s)] = w[t,s] * dy[t],  dw[t,s] = <dy[t], y_perm[row(t,s)]>.
+// KT > 0: the wavefront walks the row in pieces of 64 lanes x VEC columns; a piece of dy[t] is read once
+// and meets the same piece of all k rows, whose loads are in flight together.  Per (t,s) the products are
+// added in the same order as in the KT == 0 form: ascending columns inside a lane, then across the lanes.
+template <class T, int VEC, int KT>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ y_perm,
                                                           const int32_t* __restrict__ row_of_pair,
                                                           const float* __restrict__ w, T* __restrict__ dy_perm,
@@ -471,24 +573,58 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
     const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (t >= Tn) return;
     const int vecs_per_row = d / VEC;
-    for (int s = 0; s < k; ++s) {
-        const int row = row_of_pair[(size_t)t * k + s];
-        const float ws = w[(size_t)t * k + s];
-        float dot = 0.f;
-        for (int v = lane; v < vecs_per_row; v += 64) {
-            float g[VEC], yv[VEC], o[VEC];
-            VecIO<T, VEC>::load(dy + (size_t)t * d + (size_t)v * VEC, g);
-            VecIO<T, VEC>::load(y_perm + (size_t)row * d + (size_t)v * VEC, yv);
+    if constexpr (KT > 0) {
+        int rows[KT];
+        float ws[KT], dot[KT];
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                dot += g[j] * yv[j];
-                o[j] = ws * g[j];
+        for (int s = 0; s < KT; ++s) {
+            rows[s] = row_of_pair[(size_t)t * KT + s];
+            ws[s] = w[(size_t)t * KT + s];
+            dot[s] = 0.f;
+        }
+        for (int v = lane; v < vecs_per_row; v += 64) {
+            float g[VEC], yv[KT][VEC];
+            VecIO<T, VEC>::load(dy + (size_t)t * d + (size_t)v * VEC, g);
+#pragma unroll
+            for (int s = 0; s < KT; ++s) VecIO<T, VEC>::template load<true>(y_perm + (size_t)rows[s] * d + (size_t)v * VEC, yv[s]);
+#pragma unroll
+            for (int s = 0; s < KT; ++s) {
+                float o[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    dot[s] += g[j] * yv[s][j];
+                    o[j] = ws[s] * g[j];
+                }
+                VecIO<T, VEC>::store(dy_perm + (size_t)rows[s] * d + (size_t)v * VEC, o);
             }
-            VecIO<T, VEC>::store(dy_perm + (size_t)row * d + (size_t)v * VEC, o);
         }
 #pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
-        if (lane == 0) dw[(size_t)t * k + s] = dot;
+        for (int s = 0; s < KT; ++s) {
+            float ds = dot[s];
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) ds += __shfl_xor(ds, m, 64);
+            if (lane == 0) dw[(size_t)t * KT + s] = ds;
+        }
+    } else {
+        for (int s = 0; s < k; ++s) {
+            const int row = row_of_pair[(size_t)t * k + s];
+            const float ws = w[(size_t)t * k + s];
+            float dot = 0.f;
+            for (int v = lane; v < vecs_per_row; v += 64) {
+                float g[VEC], yv[VEC], o[VEC];
+                VecIO<T, VEC>::load(dy + (size_t)t * d + (size_t)v * VEC, g);
+                VecIO<T, VEC>::template load<true>(y_perm + (size_t)row * d + (size_t)v * VEC, yv);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    dot += g[j] * yv[j];
+                    o[j] = ws * g[j];
+                }
+                VecIO<T, VEC>::store(dy_perm + (size_t)row * d + (size_t)v * VEC, o);
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
+            if (lane == 0) dw[(size_t)t * k + s] = dot;
+        }
     }
 }
 
@@ -502,6 +638,18 @@ static inline int grid_for(int64_t work_items, int block, int max_blocks) {
 }  // namespace moe
 
 using namespace moe;
+
+// launch with k as a template argument where a specialisation exists (k = 1, 2, 4, 6, 8), else the runtime-k form
+#define MOE_DISPATCH_K(kval, CALL)      \
+    switch (kval) {                     \
+        case 1: { CALL(1); break; }     \
+        case 2: { CALL(2); break; }     \
+        case 4: { CALL(4); break; }     \
+        case 6: { CALL(6); break; }     \
+        case 8: { CALL(8); break; }     \
+        default: { CALL(0); break; }    \
+    }
+
 
 extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32_t* topk_ids, int32_t* counts,
                                   int32_t* offsets, int32_t* row_of_pair, int32_t* pair_of_row, void* x_perm,
@@ -525,16 +673,18 @@ extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32
     const int nchunks = num_chunks(R);
     const int nblocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
     int32_t* chunk_hist = static_cast<int32_t*>(ws);
-    int32_t* chunk_base = chunk_hist + align_up((size_t)nchunks * E * sizeof(int32_t), 256) / sizeof(int32_t);
     const size_t lds = (size_t)kWavesPerBlock * E * sizeof(int32_t);
     permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_pairs(R), chunk_hist);
-    permute_scan_kernel<<<1, 256, 0, st>>>(chunk_hist, chunk_base, nchunks, E, counts, offsets);
-    permute_rank_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_pairs(R), chunk_base, row_of_pair, pair_of_row);
+    permute_rank_scan_kernel<<<nblocks, kRankScanThreads, 0, st>>>(topk_ids, R, E, chunk_pairs(R), chunk_hist, nchunks,
+                                                                   counts, offsets, row_of_pair, pair_of_row);
     if (x_perm) {
         const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
         const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);
-        permute_scatter_rows_kernel<<<grid, 256, 0, st>>>(static_cast<const u32x4*>(x), row_of_pair,
-                                                          static_cast<u32x4*>(x_perm), s->T, s->k, vecs_per_row);
+#define MOE_CALL(KT)                                                                                       \
+    permute_scatter_rows_kernel<KT><<<grid, 256, 0, st>>>(static_cast<const u32x4*>(x), row_of_pair,        \
+                                                          static_cast<u32x4*>(x_perm), s->T, s->k, vecs_per_row)
+        MOE_DISPATCH_K(s->k, MOE_CALL)
+#undef MOE_CALL
     }
     return launch_status(who);
 }
@@ -583,8 +733,11 @@ extern "C" moe_status moe_permute_lite(const moe_shape* s, int32_t G, int32_t n_
     if (x_perm) {
         const int vecs_per_row = (int)((size_t)s->d * el_size(s) / 16);
         const int grid = grid_for((int64_t)s->T * vecs_per_row, 256, 256 * 16);
-        permute_scatter_rows_kernel<<<grid, 256, 0, st>>>(static_cast<const u32x4*>(x), row_of_pair,
-                                                          static_cast<u32x4*>(x_perm), s->T, s->k, vecs_per_row);
+#define MOE_CALL(KT)                                                                                       \
+    permute_scatter_rows_kernel<KT><<<grid, 256, 0, st>>>(static_cast<const u32x4*>(x), row_of_pair,        \
+                                                          static_cast<u32x4*>(x_perm), s->T, s->k, vecs_per_row)
+        MOE_DISPATCH_K(s->k, MOE_CALL)
+#undef MOE_CALL
     }
     return launch_status(who);
 }
@@ -600,12 +753,18 @@ extern "C" moe_status moe_unpermute_combine(const moe_shape* s, const void* y_pe
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (s->dtype == MOE_BF16) {
         const int grid = grid_for((int64_t)s->T * (s->d / 8), 256, 256 * 16);
-        combine_kernel<bf16_t, 8><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(y_perm), row_of_pair, topk_w,
-                                                        static_cast<bf16_t*>(y), s->T, s->d, s->k);
+#define MOE_CALL(KT)                                                                                                  \
+    combine_kernel<bf16_t, 8, KT><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(y_perm), row_of_pair, topk_w,     \
+                                                        static_cast<bf16_t*>(y), s->T, s->d, s->k)
+        MOE_DISPATCH_K(s->k, MOE_CALL)
+#undef MOE_CALL
     } else {
         const int grid = grid_for((int64_t)s->T * (s->d / 4), 256, 256 * 16);
-        combine_kernel<float, 4><<<grid, 256, 0, st>>>(static_cast<const float*>(y_perm), row_of_pair, topk_w,
-                                                       static_cast<float*>(y), s->T, s->d, s->k);
+#define MOE_CALL(KT)                                                                                                  \
+    combine_kernel<float, 4, KT><<<grid, 256, 0, st>>>(static_cast<const float*>(y_perm), row_of_pair, topk_w,       \
+                                                       static_cast<float*>(y), s->T, s->d, s->k)
+        MOE_DISPATCH_K(s->k, MOE_CALL)
+#undef MOE_CALL
     }
     return launch_status(who);
 }
@@ -623,13 +782,20 @@ extern "C" moe_status moe_combine_bwd(const moe_shape* s, const void* dy, const 
     MOE_RETURN_IF(check_ptr(dtopk_w, "dtopk_w", who));
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int grid = (s->T + 3) / 4;
-    if (s->dtype == MOE_BF16)
-        combine_bwd_kernel<bf16_t, 8><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(dy),
-                                                            static_cast<const bf16_t*>(y_perm), row_of_pair, topk_w,
-                                                            static_cast<bf16_t*>(dy_perm), dtopk_w, s->T, s->d, s->k);
-    else
-        combine_bwd_kernel<float, 4><<<grid, 256, 0, st>>>(static_cast<const float*>(dy),
-                                                           static_cast<const float*>(y_perm), row_of_pair, topk_w,
-                                                           static_cast<float*>(dy_perm), dtopk_w, s->T, s->d, s->k);
+    if (s->dtype == MOE_BF16) {
+#define MOE_CALL(KT)                                                                                                  \
+    combine_bwd_kernel<bf16_t, 8, KT><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(dy),                          \
+                                                            static_cast<const bf16_t*>(y_perm), row_of_pair, topk_w, \
+                                                            static_cast<bf16_t*>(dy_perm), dtopk_w, s->T, s->d, s->k)
+        MOE_DISPATCH_K(s->k, MOE_CALL)
+#undef MOE_CALL
+    } else {
+#define MOE_CALL(KT)                                                                                                  \
+    combine_bwd_kernel<float, 4, KT><<<grid, 256, 0, st>>>(static_cast<const float*>(dy),                            \
+                                                           static_cast<const float*>(y_perm), row_of_pair, topk_w,   \
+                                                           static_cast<float*>(dy_perm), dtopk_w, s->T, s->d, s->k)
+        MOE_DISPATCH_K(s->k, MOE_CALL)
+#undef MOE_CALL
+    }
     return launch_status(who);
 }
