@@ -343,27 +343,64 @@ __global__ void gate_dl_kernel(const float* __restrict__ w, const float* __restr
 }
 
 // dx[t,c] += sum_s dl[t,s] * wgT[ids[t,s]][c]      (4 columns per thread)
-template <class T>
+// 16 bytes of dx per thread (8 bf16 / 4 fp32 columns); KT > 0: k at compile time, the k gate-weight rows are
+// requested together with the dx piece.  d is a multiple of the vector width (checked with the shape).
+template <class T, int VEC, int KT>
 __global__ __launch_bounds__(256) void gate_bwd_dx_kernel(T* __restrict__ dx, const float* __restrict__ wgT,
                                                           const int32_t* __restrict__ ids,
                                                           const float* __restrict__ dl, int Tn, int d, int k) {
-    const int q = d / 4;
+    const int q = d / VEC;
     const int64_t total = (int64_t)Tn * q;
+    constexpr int KU = KT > 0 ? KT : 1;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x) {
-        const int t = (int)(i / q), c = (int)(i - (int64_t)t * q) * 4;
-        float a[4];
+        const int t = (int)(i / q), c = (int)(i - (int64_t)t * q) * VEC;
+        T raw[VEC];
+        static_assert(VEC * sizeof(T) == 16, "one 16-byte piece per thread");
+        *reinterpret_cast<uint4*>(raw) = *reinterpret_cast<const uint4*>(dx + (size_t)t * d + c);
+        float a[VEC];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = Elem<T>::load(dx + (size_t)t * d + c + j);
-        for (int s = 0; s < k; ++s) {
-            const float g = dl[(size_t)t * k + s];
-            const float4 wv = *reinterpret_cast<const float4*>(wgT + (size_t)ids[(size_t)t * k + s] * d + c);
-            a[0] = fmaf(g, wv.x, a[0]); a[1] = fmaf(g, wv.y, a[1]);
-            a[2] = fmaf(g, wv.z, a[2]); a[3] = fmaf(g, wv.w, a[3]);
+        for (int j = 0; j < VEC; ++j) a[j] = Elem<T>::load(raw + j);
+        if constexpr (KT > 0) {
+            float g[KU], wv[KU][VEC];
+#pragma unroll
+            for (int s = 0; s < KU; ++s) {
+                g[s] = dl[(size_t)t * KU + s];
+                const float* row = wgT + (size_t)ids[(size_t)t * KU + s] * d + c;
+#pragma unroll
+                for (int j = 0; j < VEC; j += 4) {
+                    const float4 v4 = *reinterpret_cast<const float4*>(row + j);
+                    wv[s][j] = v4.x; wv[s][j + 1] = v4.y; wv[s][j + 2] = v4.z; wv[s][j + 3] = v4.w;
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < KU; ++s)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) a[j] = fmaf(g[s], wv[s][j], a[j]);
+        } else {
+            for (int s = 0; s < k; ++s) {
+                const float g = dl[(size_t)t * k + s];
+                const float* row = wgT + (size_t)ids[(size_t)t * k + s] * d + c;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) a[j] = fmaf(g, row[j], a[j]);
+            }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) Elem<T>::store(dx + (size_t)t * d + c + j, a[j]);
+        for (int j = 0; j < VEC; ++j) Elem<T>::store(raw + j, a[j]);
+        *reinterpret_cast<uint4*>(dx + (size_t)t * d + c) = *reinterpret_cast<const uint4*>(raw);
     }
+}
+
+template <class T>
+static void launch_gate_bwd_dx(T* dx, const float* wgT, const int32_t* ids, const float* dl, int Tn, int d, int k,
+                               hipStream_t st) {
+    constexpr int VEC = 16 / sizeof(T);
+    const int64_t items = (int64_t)Tn * (d / VEC);
+    const int grid = (int)((items + 255) / 256 > 4096 ? 4096 : (items + 255) / 256);
+    if (k == 1) gate_bwd_dx_kernel<T, VEC, 1><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, Tn, d, k);
+    else if (k == 2) gate_bwd_dx_kernel<T, VEC, 2><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, Tn, d, k);
+    else if (k == 4) gate_bwd_dx_kernel<T, VEC, 4><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, Tn, d, k);
+    else gate_bwd_dx_kernel<T, VEC, 0><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, Tn, d, k);
 }
 
 // partial[chunk][e][c] = sum over the chunk's tokens of x[t,c] * dL[t,e]; a thread
@@ -594,9 +631,7 @@ static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gat
             launch_gate_dx_gemm(hi, lo, wg_pad, whole, s->d, n_pad, dx, st);
         } else if (dx) {
             gate_transpose_kernel<T><<<256, 256, 0, st>>>(w_gate, wgT, s->d, s->E);
-            int64_t items = (int64_t)s->T * (s->d / 4);
-            int grid = (int)((items + 255) / 256 > 4096 ? 4096 : (items + 255) / 256);
-            gate_bwd_dx_kernel<T><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, s->T, s->d, s->k);
+            launch_gate_bwd_dx<T>(dx, wgT, ids, dl, s->T, s->d, s->k, st);
         }
         launch_gate_dwg_gemm(x, hi, lo, coff, nch, s->d, n_pad, partial, zero_row, st);
         gate_bwd_dwg_reduce_mma_kernel<<<256, 256, 0, st>>>(partial, dwg, nch, s->d, s->E, n_pad);
@@ -605,9 +640,7 @@ static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gat
     gate_dl_kernel<<<(s->T + 255) / 256, 256, 0, st>>>(w, dw, dl, s->T, s->k);
     if (dx) {
         gate_transpose_kernel<T><<<256, 256, 0, st>>>(w_gate, wgT, s->d, s->E);
-        int64_t items = (int64_t)s->T * (s->d / 4);
-        int grid = (int)((items + 255) / 256 > 4096 ? 4096 : (items + 255) / 256);
-        gate_bwd_dx_kernel<T><<<grid, 256, 0, st>>>(dx, wgT, ids, dl, s->T, s->d, s->k);
+        launch_gate_bwd_dx<T>(dx, wgT, ids, dl, s->T, s->d, s->k, st);
     }
     const size_t lds = (size_t)s->E * kDwgSlab * sizeof(float);
     static thread_local bool attr_set = false;
