@@ -22,7 +22,10 @@ CASES = {
     "bf16_e130": dict(T=257, d=256, f=128, E=130, k=8, dtype="bf16", alpha=0.3, dead=0),
     "bf16_e256": dict(T=400, d=256, f=64, E=256, k=8, dtype="bf16", alpha=0.2, dead=0),   # the largest expert count
     "bf16_e64_wide": dict(T=700, d=512, f=320, E=64, k=4, dtype="bf16", alpha=0.4, dead=2),
+    "bf16_k6": dict(T=300, d=128, f=96, E=16, k=6, dtype="bf16", alpha=0.5, dead=1),       # k = 6 and 5: the compile-time-k
+    "bf16_k5": dict(T=190, d=64, f=128, E=9, k=5, dtype="bf16", alpha=0.7, dead=0),        # and the runtime-k row kernels
     "f32_ragged": dict(T=150, d=68, f=100, E=5, k=2, dtype="f32", alpha=1.0, dead=1),
+    "f32_k6": dict(T=90, d=36, f=20, E=7, k=6, dtype="f32", alpha=0.4, dead=0),
     "f32_tiny_T": dict(T=1, d=8, f=4, E=2, k=1, dtype="f32", alpha=0.0, dead=0),
 }
 
