@@ -228,3 +228,36 @@ def test_grouped_ffn_backward_sampled(case):
     torch.cuda.synchronize()
     for a, b in zip(ref, (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2)):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("T,k,E", [(280_000, 8, 200), (150_001, 3, 7)])
+def test_permutation_of_very_many_pairs(T, k, E):
+    """R = T*k beyond 256 chunks of the longest chunk length (and a ragged last chunk): the index outputs
+    against the oracle's stable sort, bit for bit; the rows (8 columns) as copies of their tokens."""
+    rng = np.random.default_rng(T + k)
+    p = rng.zipf(1.3, size=E).astype(np.float64)
+    p /= p.sum()
+    ids = np.empty((T, k), np.int32)
+    # k distinct experts per token: a random rotation of a skewed draw, made distinct by stepping
+    first = rng.choice(E, size=T, p=p)
+    step = rng.integers(1, E, size=T) if E > 1 else np.zeros(T, np.int64)
+    for s_ in range(k):
+        ids[:, s_] = (first + s_ * np.where(np.gcd(step, E) == 1, step, 1)) % E
+    x = rng.standard_normal((T, 8)).astype(np.float32)
+    counts, offsets, rop, por, xp = O.permute(x, ids, E)
+    s = B.Shape(T, 8, 8, E, k, torch.float32)
+    gx, gids = torch.from_numpy(x).cuda(), torch.from_numpy(ids).cuda()
+    g_counts = torch.empty(E, dtype=torch.int32, device="cuda")
+    g_offsets = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    g_rop = torch.empty(T * k, dtype=torch.int32, device="cuda")
+    g_por = torch.empty(T * k, dtype=torch.int32, device="cuda")
+    g_xp = torch.empty(T * k, 8, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    print(f"[full-size] permutation of {T * k} pairs", flush=True)
+    B.moe_permute(s, gx, gids, g_counts, g_offsets, g_rop, g_por, g_xp, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(g_counts), counts)
+    np.testing.assert_array_equal(host(g_offsets), offsets)
+    np.testing.assert_array_equal(host(g_rop), rop)
+    np.testing.assert_array_equal(host(g_por), por)
+    np.testing.assert_array_equal(host(g_xp), xp)
