@@ -7,10 +7,16 @@ One step = one pass of the hot path over one batch of the named synthetic
 workload: gate -> permute -> grouped FFN forward -> combine, plus (for the
 workloads that train) combine backward -> grouped FFN backward -> permute
 backward -> gate backward.  Inputs are resident in HBM before the timed region.
+The default workload is the Mixtral-8x7B-shaped layer at 16K tokens per device,
+forward + backward (the largest configuration that the metric is quoted on).
 Prints ONE JSON line.  `value` is tokens/s of the whole step; `roofline` prices
 the grouped-FFN kernels (the dominant ones) against the dense bf16 MFMA peak
-with HIP events recorded around them inside the timed steps; `cpu_baseline` is
-the CPU oracle timed on a bounded sample of the same workload.
+with HIP events recorded around them inside the timed steps; `roofline_hbm`
+prices the row-copy stages against the HBM peak; `other_workloads` holds the
+same figures for the other configurations (fewer steps); `ceilings` are what a
+plain device copy and a dense one-expert problem through the same GEMM kernel
+reach on this machine in this run; `cpu_baseline` is the CPU oracle timed on a
+bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -201,47 +207,19 @@ def fsep_leg(w, counts, N=8, D=8):
             "v_fsep_bytes_per_rank": C * (N - 1) * (psi // N) * el}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2_e64k4")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--hot-path-only", action="store_true",
-                    help="time the layer only: no cold-cache, dispatcher, FSEP or CPU legs (what the profiles are taken on)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="run only a plain 1 GiB device copy a few times (reference for the HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build is single-GPU by design (the hot path of one device's token share); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(w, steps, warmup, inp=None, keep=False):
+    """`warmup` untimed steps, then `steps` timed steps of the hot path on workload w.
+    Returns the figures of the run (and, with keep, the device tensors for the legs that follow)."""
     import numpy as np
     import torch
     from paper_2602_11686_amd import binding as B
     from paper_2602_11686_amd import inputs as I
     from paper_2602_11686_amd.layer import MoeLayerBuffers, to_device
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
-        sys.exit(3)
-    B.lib()  # fail loudly if the HIP library is not built
-
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "repeats": 5}))
-        return
-
-    w = I.WORKLOADS[args.workload]
     dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     s = B.Shape(w.T, w.d, w.f, w.E, w.k, dt)
-    inp = I.layer_inputs(w)
+    if inp is None:
+        inp = I.layer_inputs(w)
     g = {n: (to_device(v, dt) if n != "bias" else torch.from_numpy(v).cuda()) for n, v in inp.items()}
     buf = MoeLayerBuffers(s, backward=w.backward)
     torch.cuda.synchronize()
@@ -249,7 +227,7 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stage_names = ["gate", "permute", "ffn_fwd", "combine"] + (
         ["combine_bwd", "ffn_bwd", "permute_bwd", "gate_bwd"] if w.backward else [])
-    marks = [[ev() for _ in range(len(stage_names) + 1)] for _ in range(args.steps)]
+    marks = [[ev() for _ in range(len(stage_names) + 1)] for _ in range(steps)]
 
     def step(m=None):
         def mark(i):
@@ -270,17 +248,17 @@ def main():
             B.moe_gate_topk_bwd(s, g["x"], g["w_gate"], buf.topk_ids, buf.topk_w, buf.dtopk_w, buf.dx,
                                 buf.dw_gate, buf.ws); mark(8)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(marks[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    ms_per_step = wall * 1e3 / args.steps
-    stage_ms = {n: float(np.mean([marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(args.steps)]))
+    ms_per_step = wall * 1e3 / steps
+    stage_ms = {n: float(np.mean([marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(steps)]))
                 for j, n in enumerate(stage_names)}
     counts = buf.counts.cpu().numpy()
     R, el = w.T * w.k, (2 if w.dtype == "bf16" else 4)
@@ -293,42 +271,187 @@ def main():
     achieved = flops / (ffn_ms * 1e-3) / 1e12
     perm_bytes = (1 + w.k) * w.T * w.d * el + R * 12
     comb_bytes = (1 + w.k) * w.T * w.d * el + R * 8
+    cbwd_bytes = (1 + 2 * w.k) * w.T * w.d * el
     stages = {n: {"ms": round(v, 4)} for n, v in stage_ms.items()}
     stages["ffn_fwd"]["tflops"] = round(ffn_fwd_flops / (stage_ms["ffn_fwd"] * 1e-3) / 1e12, 2)
-    stages["permute"]["gbs"] = round(perm_bytes / (stage_ms["permute"] * 1e-3) / 1e9, 1)
-    stages["combine"]["gbs"] = round(comb_bytes / (stage_ms["combine"] * 1e-3) / 1e9, 1)
+    hbm = {}
+
+    def hbm_stage(name, nbytes):
+        gbs = nbytes / (stage_ms[name] * 1e-3) / 1e9
+        stages[name]["gbs"] = round(gbs, 1)
+        hbm[name] = {"achieved": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_launch": nbytes}
+    hbm_stage("permute", perm_bytes)
+    hbm_stage("combine", comb_bytes)
     if w.backward:
         stages["ffn_bwd"]["tflops"] = round(ffn_bwd_flops / (stage_ms["ffn_bwd"] * 1e-3) / 1e12, 2)
-        stages["permute_bwd"]["gbs"] = round(comb_bytes / (stage_ms["permute_bwd"] * 1e-3) / 1e9, 1)
-        stages["combine_bwd"]["gbs"] = round(((1 + 2 * w.k) * w.T * w.d * el) / (stage_ms["combine_bwd"] * 1e-3) / 1e9, 1)
+        hbm_stage("permute_bwd", comb_bytes)
+        hbm_stage("combine_bwd", cbwd_bytes)
+    res = {"ms_per_step": ms_per_step, "tokens_per_s": w.T / (ms_per_step * 1e-3), "stages": stages, "hbm": hbm,
+           "achieved": achieved, "flops": flops, "ffn_ms": ffn_ms, "counts": counts,
+           "perm_bytes": perm_bytes, "comb_bytes": comb_bytes,
+           "config": {"workload": w.name, "T": w.T, "d": w.d, "f": w.f, "E": w.E, "k": w.k,
+                      "pass": "fwd+bwd" if w.backward else "fwd", "seed": w.seed,
+                      "max_over_mean_load": float(counts.max() / counts.mean()),
+                      "empty_experts": int((counts == 0).sum())}}
+    if keep:
+        res["live"] = (s, g, buf, inp)
+    return res
 
-    traffic = None
+
+def ceilings_leg():
+    """What this machine gives, in this run, to (i) a plain device-to-device copy of 1 GiB (read + write, beyond the
+    256 MB memory-side cache) and (ii) a dense one-expert problem (8192 rows, d = f = 4096, forward and
+    backward) through the same grouped-GEMM kernels: the measured ceilings beside the vendor peaks."""
+    import torch
+    from paper_2602_11686_amd import binding as B
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * (1 << 30) * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    T, d, f = 8192, 4096, 4096
+    s = B.Shape(T, d, f, 1, 1, torch.bfloat16)
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    rn = lambda *sh: (torch.randn(sh, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+    xp, dyp, w1, w3, w2 = rn(T, d) * 50, rn(T, d) * 50, rn(1, d, f), rn(1, d, f), rn(1, f, d)
+    off = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    yp, dxp = torch.empty_like(xp), torch.empty_like(xp)
+    a, b = torch.empty(T, f, dtype=torch.bfloat16, device="cuda"), torch.empty(T, f, dtype=torch.bfloat16, device="cuda")
+    dw1, dw3, dw2 = torch.empty_like(w1), torch.empty_like(w3), torch.empty_like(w2)
+    fwd = lambda: B.moe_grouped_ffn_fwd(s, xp, off, w1, w3, w2, yp, a, b, ws)
+    bwd = lambda: B.moe_grouped_ffn_bwd(s, xp, off, w1, w3, w2, a, b, dyp, dxp, dw1, dw3, dw2, ws)
+    out = {"copy_1GiB_gbs": round(copy_gbs, 1), "copy_frac_of_hbm_peak": round(copy_gbs / PEAK_HBM_GBS, 4)}
+    for name, fn, fl in (("dense_gemm_fwd_tflops", fwd, 6.0 * T * d * f), ("dense_gemm_bwd_tflops", bwd, 12.0 * T * d * f)):
+        for _ in range(3):
+            fn()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(fl * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    out["dense_gemm_shape"] = {"rows": T, "d": d, "f": f, "experts": 1}
+    return out
+
+
+OTHER_WORKLOADS = ["cfg2_e64k4", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced"]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3_mixtral")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other configurations (other_workloads)")
+    ap.add_argument("--hot-path-only", action="store_true",
+                    help="time the layer only: no cold-cache, dispatcher, FSEP, ceiling, other-workload or CPU legs "
+                         "(what the profiles are taken on)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy a few times (reference for the HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the hot path of one device's token share); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_11686_amd import binding as B
+    from paper_2602_11686_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    B.lib()  # fail loudly if the HIP library is not built
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "repeats": 5}))
+        return
+
+    w = I.WORKLOADS[args.workload]
+    r = run_workload(w, args.steps, args.warmup, keep=True)
+    s, g, buf, inp = r.pop("live")
+    counts = r["counts"]
+
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):  # HBM bytes of the grouped-FFN kernels measured with rocprofv3 --pmc (see profiles/)
+    if os.path.exists(tpath):  # bytes between L2 and the fabric for the grouped-FFN kernels, rocprofv3 --pmc (profiles/)
         with open(tpath) as fh:
-            traffic = json.load(fh).get(w.name, {}).get("ffn_hbm_bytes_per_step")
+            rec = json.load(fh).get(w.name, {})
+        traffic = rec.get("ffn_hbm_bytes_per_step")
+        if traffic is not None:
+            traffic_source = "profiles/traffic.json (committed rocprofv3 --pmc run, not measured in this run): " + rec.get("source", "")
 
     out = {
         "metric": "MoE-layer tokens/s; grouped-GEMM bf16 TFLOP/s and % MFMA peak, 1 GPU",
-        "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "T": w.T, "d": w.d, "f": w.f, "E": w.E, "k": w.k,
-                   "pass": "fwd+bwd" if w.backward else "fwd", "seed": w.seed,
-                   "max_over_mean_load": float(counts.max() / counts.mean()),
-                   "empty_experts": int((counts == 0).sum())},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+        "config": r["config"],
+        "roofline": {"bound": "mfma", "achieved": r["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": r["achieved"] / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "grouped FFN (moe_grouped_ffn_fwd" + ("+bwd" if w.backward else "") + ")",
-                     "flops_per_launch": flops, "ms_per_launch": ffn_ms},
-        "stages": stages,
+                     "flops_per_launch": r["flops"], "ms_per_launch": r["ffn_ms"]},
+        "roofline_hbm": {"bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s", "stages": r["hbm"]},
+        "stages": r["stages"],
     }
     if not args.hot_path_only:
-        out["cold_cache"] = cold_leg(w, s, g, buf, perm_bytes, comb_bytes)
+        out["cold_cache"] = cold_leg(w, s, g, buf, r["perm_bytes"], r["comb_bytes"])
+        for n in ("permute", "combine"):
+            out["cold_cache"][n]["frac"] = round(out["cold_cache"][n]["gbs"] / PEAK_HBM_GBS, 4)
         out["dispatcher"] = dispatcher_leg(w, s, g, buf, counts)
         out["fsep_layout"] = fsep_leg(w, counts)
+    cpu = None
     if not args.no_cpu_baseline and not args.hot_path_only:
-        out["cpu_baseline"] = cpu_baseline(w, inp)
+        cpu = cpu_baseline(w, inp)
+    del s, g, buf, inp
+    torch.cuda.empty_cache()
+    if not args.hot_path_only:
+        out["ceilings"] = ceilings_leg()
+        torch.cuda.empty_cache()
+    if not args.hot_path_only and not args.no_other_workloads:
+        others, shared = {}, {}
+        for name in OTHER_WORKLOADS:
+            if name == w.name:
+                continue
+            ow = I.WORKLOADS[name]
+            # the two routings of the re-layout comparison share tokens and weights (same seed); only the bias differs
+            key = (ow.seed, ow.T, ow.d, ow.f, ow.E, ow.k, ow.dtype)
+            oinp = shared.get(key)
+            if oinp is None:
+                shared.clear()
+                oinp = shared[key] = I.layer_inputs(ow)
+            oinp = dict(oinp, bias=I.gate_bias(ow))
+            o = run_workload(ow, steps=20, warmup=5, inp=oinp)
+            others[name] = {"ms_per_step": round(o["ms_per_step"], 4), "tokens_per_s": round(o["tokens_per_s"], 1),
+                            "pass": o["config"]["pass"], "max_over_mean_load": o["config"]["max_over_mean_load"],
+                            "empty_experts": o["config"]["empty_experts"], "steps": 20, "warmup": 5,
+                            "ffn_tflops": round(o["achieved"], 1), "frac": round(o["achieved"] / PEAK_BF16_TFLOPS, 4),
+                            "hbm": {n: {"gbs": v["achieved"], "frac": v["frac"]} for n, v in o["hbm"].items()}}
+            torch.cuda.empty_cache()
+        if "cfg5_skewed" in others and "cfg5_balanced" in others:
+            others["cfg5_skewed_over_balanced_step_time"] = round(
+                others["cfg5_skewed"]["ms_per_step"] / others["cfg5_balanced"]["ms_per_step"], 4)
+        out["other_workloads"] = others
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

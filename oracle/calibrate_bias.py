@@ -7,7 +7,8 @@ oracle's gate sends ``target_ratio`` times the mean load to the busiest expert
 the HIP path is never involved.  The stored file is an *input* recipe constant
 (like a seed), not an expected output.
 
-    python -m oracle.calibrate_bias
+    python -m oracle.calibrate_bias          # only the workloads that have no stored constant yet
+    python -m oracle.calibrate_bias --all    # every workload again
 """
 from __future__ import annotations
 
@@ -28,9 +29,15 @@ def ratio_for(w, X, Wg, alpha):
 
 
 def main():
+    import sys
+    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                        "paper_2602_11686_amd", "bias_alpha.json")
     out = {}
+    if "--all" not in sys.argv[1:] and os.path.exists(path):
+        with open(path) as fh:
+            out = json.load(fh)
     for name, w in I.WORKLOADS.items():
-        if w.target_ratio is None:
+        if w.target_ratio is None or name in out:
             continue
         X = I.widen(I.tokens(w))
         Wg = I.widen(I.gate_weight(w))
@@ -49,8 +56,6 @@ def main():
         out[name] = {"alpha": alpha, "max_over_mean": float(r), "empty_experts": int((counts == 0).sum()),
                      "counts_sorted": sorted((int(c) for c in counts), reverse=True)}
         print(name, out[name]["alpha"], out[name]["max_over_mean"], out[name]["empty_experts"], flush=True)
-    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
-                        "paper_2602_11686_amd", "bias_alpha.json")
     with open(path, "w") as fh:
         json.dump(out, fh, indent=1)
     print("wrote", path)

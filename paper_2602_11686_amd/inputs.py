@@ -79,7 +79,7 @@ def _wl(name, T, d, f, E, k, dtype, seed, zipf_s, alpha=None, **kw) -> Workload:
     return Workload(name, T, d, f, E, k, dtype, seed, zipf_s, a, **kw)
 
 
-# The five workloads; alpha of the calibrated ones comes from bias_alpha.json
+# The five workloads (and the extra layer shapes below them); alpha of the calibrated ones comes from bias_alpha.json
 # (written by oracle/calibrate_bias.py).  cfg1's bias is fixed by its recipe:
 # 0.5*ln(rank^-1.2) = -0.6*ln(rank)  ->  s = 1.2, alpha = 0.5.
 WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
@@ -92,6 +92,17 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     _wl("cfg5_skewed", 16384, 4096, 14336, 8, 2, "bf16", 4, 1.0, target_ratio=3.0,
         backward=True),
     _wl("cfg5_balanced", 16384, 4096, 14336, 8, 2, "bf16", 4, 1.0, alpha=0.0,
+        backward=True),
+    # The other layer shapes of the paper's table "Configurations of the evaluated models" (same 16K tokens
+    # per device, same Zipf-biased gate as cfg3).  e16k4 keeps a layer's parameter count and its compute per
+    # token: twice the experts and twice the top-k at half the intermediate size.  The table prints no hidden
+    # sizes for Mixtral-8x22B; d = 6144, f = 16384 is the reading that reproduces its 45.46 B parameters over
+    # 18 layers (8 * 3 * d * f = 2.42 B per MoE layer).  A Qwen-8x7B MoE layer has the shape of cfg3.
+    _wl("mixtral8x7b_e16k4", 16384, 4096, 7168, 16, 4, "bf16", 5, 1.0, target_ratio=2.5,
+        backward=True),
+    _wl("mixtral8x22b_e8k2", 16384, 6144, 16384, 8, 2, "bf16", 6, 1.0, target_ratio=2.5,
+        backward=True),
+    _wl("mixtral8x22b_e16k4", 16384, 6144, 8192, 16, 4, "bf16", 7, 1.0, target_ratio=2.5,
         backward=True),
 ]}
 

@@ -65,3 +65,28 @@ def check_gate(ids_gpu, w_gpu, logits_gpu, ref_ids, ref_w, ref_logits, k):
     assert np.abs(w_gpu[same] - ref_w[same]).max() <= 2e-6 + 1e-5
     np.testing.assert_allclose(w_gpu.sum(1), 1.0, atol=1e-5)
     return int((~safe).sum())
+
+
+def follow_gpu_ids(o, w, fw, ids_gpu):
+    """The oracle's staged layer with the GPU's (validated) choice taken for the near-tie tokens.
+
+    check_gate has accepted a token whose ids differ from the oracle's only if the gaps between the
+    logits involved are below the accumulation noise and the GPU's ids are the sorted top-k of its own
+    logits; downstream parity of such a token is defined on the ids the GPU returned.  The gate weights
+    of those tokens are the softmax of the ORACLE's logits over the chosen experts.
+    Returns (forward dict, backward dict or None, number of tokens that differ)."""
+    from scipy.special import softmax
+    differ = (ids_gpu != fw["ids"]).any(axis=1)
+    if not differ.any():
+        return fw, None, 0
+    ids = np.where(differ[:, None], ids_gpu, fw["ids"]).astype(np.int32)
+    tw = fw["w"].copy()
+    sel = np.take_along_axis(fw["logits"][differ], ids_gpu[differ].astype(np.int64), axis=1)
+    tw[differ] = softmax(sel, axis=1).astype(tw.dtype)
+    counts, offsets, rop, por, Xp = O.permute(o["x"], ids, w.E)
+    Yp, A, Bm, H = O.ffn_fwd(Xp, offsets, o["w1"], o["w3"], o["w2"])
+    Y = O.unpermute_combine(Yp, rop, tw, w.T)
+    fw2 = dict(ids=ids, w=tw, logits=fw["logits"], counts=counts, offsets=offsets, row_of_pair=rop,
+               pair_of_row=por, Xp=Xp, Yp=Yp, A=A, B=Bm, H=H, Y=Y)
+    bw2 = O.layer_bwd(o["x"], o["w_gate"], o["w1"], o["w3"], o["w2"], fw2, o["dy"]) if "dy" in o else None
+    return fw2, bw2, int(differ.sum())

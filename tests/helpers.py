@@ -12,6 +12,28 @@ def rel_max(got, ref):
     return float(np.abs(got - ref).max() / den)
 
 
+def rel_max_blocks(got, ref, blocks):
+    """The same metric taken block by block: every block (an expert's gradient matrix, an expert's
+    group of rows) is normalised by the largest reference magnitude inside that block, so that a
+    block whose values are small next to the rest of the tensor cannot hide behind it.
+    `blocks` is an iterable of index expressions into both arrays; empty blocks are skipped.
+    Returns (worst error, index of the worst block)."""
+    worst, where = 0.0, None
+    for i, b in enumerate(blocks):
+        r = np.asarray(ref[b], dtype=np.float64)
+        if r.size == 0:
+            continue
+        e = rel_max(np.asarray(got[b], dtype=np.float64), r)
+        if e > worst:
+            worst, where = e, i
+    return worst, where
+
+
+def row_blocks(offsets):
+    """One slice of rows per expert (the experts' groups of a permuted tensor)."""
+    return [slice(int(offsets[e]), int(offsets[e + 1])) for e in range(len(offsets) - 1)]
+
+
 def tiny_problem(seed, T=12, d=16, f=24, E=4, k=2, dtype=np.float64, wstd=0.3, bias=True):
     g = np.random.default_rng(seed)
     X = g.standard_normal((T, d)).astype(dtype)

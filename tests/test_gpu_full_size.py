@@ -19,11 +19,12 @@ from paper_2602_11686_amd import binding as B
 from paper_2602_11686_amd import inputs as I
 from paper_2602_11686_amd.layer import MoeLayerBuffers
 from gpu_common import TOL, check_gate, dev, host, shape_of, tdtype
-from helpers import rel_max
+from helpers import rel_max, rel_max_blocks
 
 pytestmark = pytest.mark.gpu
 
-WORKLOADS = ["cfg1_tiny_f32", "cfg2_e64k4", "cfg3_mixtral", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced"]
+WORKLOADS = ["cfg1_tiny_f32", "cfg2_e64k4", "cfg3_mixtral", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced",
+             "mixtral8x7b_e16k4", "mixtral8x22b_e8k2", "mixtral8x22b_e16k4"]
 
 
 class Case:
@@ -76,6 +77,11 @@ class Case:
                     rows.update(range(b, en, max(1, (en - b) // 8)))
         rows.update(self.rng.integers(0, w.R, n_random).tolist())
         return np.array(sorted(rows), dtype=np.int64)
+
+    def sample_blocks(self, rows):
+        """index arrays into `rows`, one per expert that has sampled rows (for the per-expert error metric)"""
+        e_of = np.searchsorted(self.offsets, rows, side="right") - 1
+        return [np.nonzero(e_of == e)[0] for e in np.unique(e_of)]
 
     def oracle_ffn_rows(self, rows, dyp_rows=None):
         """exact Yp (and dXp) of the given rows: the FFN restricted to those rows, expert by expert"""
@@ -142,6 +148,8 @@ def test_layer_forward_sampled_tokens(case):
     tol = TOL[tdtype(w)]
     yp_gpu = host(buf.y_perm[torch.from_numpy(rows).cuda()])
     assert rel_max(yp_gpu, yp_ref) <= tol
+    err, b = rel_max_blocks(yp_gpu, yp_ref, case.sample_blocks(rows))   # every expert's rows on their own scale
+    assert err <= tol, ("Yp", "expert block", b, err)
     pos = {int(r): i for i, r in enumerate(rows)}
     y_ref = np.zeros((len(toks), w.d))
     for i, t in enumerate(toks):
@@ -193,17 +201,24 @@ def test_grouped_ffn_backward_sampled(case):
     B.moe_permute(s, g["x"], ids, buf.counts, buf.offsets, buf.row_of_pair, buf.pair_of_row, buf.x_perm, buf.ws)
     gen = torch.Generator(device="cuda").manual_seed(4321 + w.seed)
     dyp = torch.randn((w.R, w.d), device="cuda", generator=gen).to(tdtype(w))
+    for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
+        t.fill_(float("nan"))                      # every element of the outputs has to be written
     B.moe_grouped_ffn_fwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.y_perm, buf.a_save, buf.b_save,
                           buf.ws)
     B.moe_grouped_ffn_bwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.a_save, buf.b_save, dyp,
                           buf.dx_perm, buf.dw1, buf.dw3, buf.dw2, buf.ws)
     torch.cuda.synchronize()
+    for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
+        assert bool(torch.isfinite(t).all())
     tol = TOL[tdtype(w)]
     # (1) whole rows of dXp
     rows = case.sample_rows(24 if w.d * w.f > 2 ** 24 else 96)
     dyp_rows = host(dyp[torch.from_numpy(rows).cuda()]).astype(np.float32)
     _, dxp_ref = case.oracle_ffn_rows(rows, dyp_rows)
-    assert rel_max(host(buf.dx_perm[torch.from_numpy(rows).cuda()]), dxp_ref) <= tol
+    dxp_gpu = host(buf.dx_perm[torch.from_numpy(rows).cuda()])
+    assert rel_max(dxp_gpu, dxp_ref) <= tol
+    err, b = rel_max_blocks(dxp_gpu, dxp_ref, case.sample_blocks(rows))
+    assert err <= tol, ("dXp", "expert block", b, err)
     # (2) weight gradients on a subset J of the intermediate channels, over all rows
     print(f"[full-size] {w.name}: oracle wgrad on a channel subset", flush=True)
     nJ = 16 if w.d * w.f > 2 ** 24 else 48
@@ -215,9 +230,15 @@ def test_grouped_ffn_backward_sampled(case):
     dyp32 = host(dyp).astype(np.float32)
     _, dW1, dW3, dW2 = O.ffn_bwd(xp32, case.offsets, W1, W3, W2, dyp32)
     Jt = torch.from_numpy(J).cuda()
-    assert rel_max(host(buf.dw1[:, :, Jt]), dW1) <= tol
-    assert rel_max(host(buf.dw3[:, :, Jt]), dW3) <= tol
-    assert rel_max(host(buf.dw2[:, Jt, :]), dW2) <= tol
+    light = np.argsort(case.counts)[: min(w.E, 8)]
+    print(f"[full-size] {w.name}: lightest experts have {case.counts[light].tolist()} rows", flush=True)
+    for name, got, want in (("dW1", buf.dw1[:, :, Jt], dW1), ("dW3", buf.dw3[:, :, Jt], dW3),
+                            ("dW2", buf.dw2[:, Jt, :], dW2)):
+        got = host(got)
+        assert rel_max(got, want) <= tol, name
+        # every expert's gradient block against that expert's own scale (the lightest experts included)
+        err, e = rel_max_blocks(got, want, range(w.E))
+        assert err <= tol, (name, "expert", e, "rows", int(case.counts[e]), err)
     for e in np.nonzero(case.counts == 0)[0]:
         assert float(buf.dw1[e].abs().max()) == 0 and float(buf.dw3[e].abs().max()) == 0 \
             and float(buf.dw2[e].abs().max()) == 0

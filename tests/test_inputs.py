@@ -40,7 +40,8 @@ def test_cfg1_bias_is_the_fixed_zipf_recipe():
     np.testing.assert_allclose(b, 0.5 * np.log(rank.astype(np.float64) ** -1.2), rtol=1e-6)
 
 
-@pytest.mark.parametrize("name", ["cfg2_e64k4", "cfg3_mixtral", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced"])
+@pytest.mark.parametrize("name", ["cfg2_e64k4", "cfg3_mixtral", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced",
+                                  "mixtral8x7b_e16k4", "mixtral8x22b_e8k2", "mixtral8x22b_e16k4"])
 def test_stored_alpha_gives_the_stated_skew(name):
     w = I.WORKLOADS[name]
     ids, _, _ = O.gate_topk(I.widen(I.tokens(w)), I.widen(I.gate_weight(w)), I.gate_bias(w), w.k)
