@@ -109,6 +109,24 @@ moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* top
                        int32_t* row_of_pair /*[R]*/, int32_t* pair_of_row /*[R]*/,
                        void* x_perm /*[R,d] el or NULL*/, void* ws, size_t ws_bytes, void* stream);
 
+/* moe_permute for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
+ * kernels as moe_permute, without `ws`: the per-chunk histograms of the counting sort live in a
+ * file-scope device array inside the library (256 KiB on every GPU that runs the library, held until the
+ * process ends).  The call allocates nothing and frees nothing; the first call on a device looks the
+ * array's address up once (hipGetSymbolAddress) and later calls reuse it.
+ * Limit: chunks(T*k) * E <= moe_permute_static_max_hist_entries() (65536), where the T*k pairs are cut
+ * into chunks of 128 pairs, doubled until at most 256 chunks remain; all shapes with T*k <= 2^21 and
+ * E <= 256 fit.  A larger problem returns MOE_ERR_UNSUPPORTED and launches nothing.
+ * All calls on one GPU share the array, which keeps the previous call's contents (nothing in it has to
+ * start at zero: every entry read is written first by the same call): two calls that overlap in time on
+ * one GPU - different streams, different host threads - race; calls on one stream are ordered. */
+size_t moe_permute_static_max_hist_entries(void);
+moe_status moe_permute_static(const moe_shape* shape, const void* x, const int32_t* topk_ids,
+                              int32_t* counts /*[E]*/, int32_t* offsets /*[E+1]*/,
+                              int32_t* row_of_pair /*[R]*/, int32_t* pair_of_row /*[R]*/,
+                              void* x_perm /*[R,d] el or NULL*/, void* stream);
+
 /* Expert computation, forward (section 3.1: SwiGLU MLP; per device the work is
  * 6*d*f FLOPs per routed row).  For every expert e and its rows
  * r in [offsets[e], offsets[e+1]):

@@ -24,8 +24,11 @@ MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = [
     "moe_status_string", "moe_last_error", "moe_abi_version", "moe_workspace_bytes", "moe_gate_topk",
     "moe_permute", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_combine_bwd",
-    "moe_gate_topk_bwd", "moe_permute_lite", "moe_grouped_ffn_fwd_groups",
+    "moe_gate_topk_bwd", "moe_permute_lite", "moe_grouped_ffn_fwd_groups", "moe_permute_static",
+    "moe_permute_static_max_hist_entries",
 ]
+_NOT_A_STATUS = {"moe_status_string", "moe_last_error", "moe_abi_version", "moe_workspace_bytes",
+                 "moe_permute_static_max_hist_entries"}
 
 
 class MoeError(RuntimeError):
@@ -71,8 +74,11 @@ def lib() -> ctypes.CDLL:
         L.moe_last_error.restype = ctypes.c_char_p
         L.moe_workspace_bytes.restype = ctypes.c_size_t
         L.moe_workspace_bytes.argtypes = [ctypes.POINTER(_CShape)]
-        for name in EXPORTS[4:]:
-            getattr(L, name).restype = ctypes.c_int
+        L.moe_permute_static_max_hist_entries.restype = ctypes.c_size_t
+        L.moe_permute_static_max_hist_entries.argtypes = []
+        for name in EXPORTS:
+            if name not in _NOT_A_STATUS:
+                getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -138,6 +144,23 @@ def moe_permute(s: Shape, x, topk_ids, counts, offsets, row_of_pair, pair_of_row
                              _ptr(pair_of_row, torch.int32, (s.R,), "pair_of_row"),
                              _ptr(x_perm, s.dtype, (s.R, s.d), "x_perm"), wp, wn, _stream()),
            "moe_permute")
+
+
+def moe_permute_static_max_hist_entries() -> int:
+    return int(lib().moe_permute_static_max_hist_entries())
+
+
+def moe_permute_static(s: Shape, x, topk_ids, counts, offsets, row_of_pair, pair_of_row, x_perm):
+    """moe_permute without a workspace: scratch in a static device array of the library (allocates nothing)."""
+    c = s.c()
+    _check(lib().moe_permute_static(ctypes.byref(c), _ptr(x, s.dtype, (s.T, s.d), "x"),
+                                    _ptr(topk_ids, torch.int32, (s.T, s.k), "topk_ids"),
+                                    _ptr(counts, torch.int32, (s.E,), "counts"),
+                                    _ptr(offsets, torch.int32, (s.E + 1,), "offsets"),
+                                    _ptr(row_of_pair, torch.int32, (s.R,), "row_of_pair"),
+                                    _ptr(pair_of_row, torch.int32, (s.R,), "pair_of_row"),
+                                    _ptr(x_perm, s.dtype, (s.R, s.d), "x_perm"), _stream()),
+           "moe_permute_static")
 
 
 def moe_grouped_ffn_fwd(s: Shape, x_perm, offsets, w1, w3, w2, y_perm, a_save, b_save, ws):

@@ -20,6 +20,8 @@
 // one-workgroup kernel of its own, because it also checks and expands the
 // replica table there.  A last kernel copies the rows: one pass over x, k row
 // writes per token.
+#include <mutex>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -651,28 +653,14 @@ using namespace moe;
     }
 
 
-extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32_t* topk_ids, int32_t* counts,
-                                  int32_t* offsets, int32_t* row_of_pair, int32_t* pair_of_row, void* x_perm,
-                                  void* ws, size_t ws_bytes, void* stream) {
-    const char* who = "moe_permute";
-    MOE_RETURN_IF(check_shape(s, who));
-    MOE_RETURN_IF(check_ptr(topk_ids, "topk_ids", who));
-    MOE_RETURN_IF(check_ptr(counts, "counts", who));
-    MOE_RETURN_IF(check_ptr(offsets, "offsets", who));
-    MOE_RETURN_IF(check_ptr(row_of_pair, "row_of_pair", who));
-    MOE_RETURN_IF(check_ptr(pair_of_row, "pair_of_row", who));
-    MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who, true));
-    if (x_perm) MOE_RETURN_IF(check_ptr(x, "x", who));
-    MOE_RETURN_IF(check_ptr(ws, "ws", who));
-    if (ws_bytes < permute_workspace_bytes(s)) {
-        set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, permute_workspace_bytes(s));
-        return MOE_ERR_WORKSPACE_TOO_SMALL;
-    }
-    hipStream_t st = static_cast<hipStream_t>(stream);
+// The kernels of moe_permute; chunk_hist: nchunks * E int32 of device memory that needs no initialisation
+// (every entry that is read is written by the histogram kernel first).
+static moe_status permute_launch(const char* who, const moe_shape* s, const void* x, const int32_t* topk_ids,
+                                 int32_t* counts, int32_t* offsets, int32_t* row_of_pair, int32_t* pair_of_row,
+                                 void* x_perm, int32_t* chunk_hist, hipStream_t st) {
     const int R = s->T * s->k, E = s->E;
     const int nchunks = num_chunks(R);
     const int nblocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
-    int32_t* chunk_hist = static_cast<int32_t*>(ws);
     const size_t lds = (size_t)kWavesPerBlock * E * sizeof(int32_t);
     permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_ids, R, E, chunk_pairs(R), chunk_hist);
     permute_rank_scan_kernel<<<nblocks, kRankScanThreads, 0, st>>>(topk_ids, R, E, chunk_pairs(R), chunk_hist, nchunks,
@@ -687,6 +675,88 @@ extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32
 #undef MOE_CALL
     }
     return launch_status(who);
+}
+
+static moe_status permute_check_args(const char* who, const moe_shape* s, const void* x, const int32_t* topk_ids,
+                                     int32_t* counts, int32_t* offsets, int32_t* row_of_pair, int32_t* pair_of_row,
+                                     void* x_perm) {
+    MOE_RETURN_IF(check_shape(s, who));
+    MOE_RETURN_IF(check_ptr(topk_ids, "topk_ids", who));
+    MOE_RETURN_IF(check_ptr(counts, "counts", who));
+    MOE_RETURN_IF(check_ptr(offsets, "offsets", who));
+    MOE_RETURN_IF(check_ptr(row_of_pair, "row_of_pair", who));
+    MOE_RETURN_IF(check_ptr(pair_of_row, "pair_of_row", who));
+    MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who, true));
+    if (x_perm) MOE_RETURN_IF(check_ptr(x, "x", who));
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_permute(const moe_shape* s, const void* x, const int32_t* topk_ids, int32_t* counts,
+                                  int32_t* offsets, int32_t* row_of_pair, int32_t* pair_of_row, void* x_perm,
+                                  void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "moe_permute";
+    MOE_RETURN_IF(permute_check_args(who, s, x, topk_ids, counts, offsets, row_of_pair, pair_of_row, x_perm));
+    MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    if (ws_bytes < permute_workspace_bytes(s)) {
+        set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, permute_workspace_bytes(s));
+        return MOE_ERR_WORKSPACE_TOO_SMALL;
+    }
+    return permute_launch(who, s, x, topk_ids, counts, offsets, row_of_pair, pair_of_row, x_perm,
+                          static_cast<int32_t*>(ws), static_cast<hipStream_t>(stream));
+}
+
+// ---- moe_permute for callers that cannot allocate ------------------------------------------------------
+// The per-chunk histograms live in a file-scope device array instead of a caller's workspace.  Every GPU
+// that loads the library holds its own copy of the array at its own address; in host code the array's name
+// is only a handle for hipGetSymbolAddress, never a device address.  The address is looked up once per
+// device (with that device current) and kept; the kernels receive it as an ordinary pointer argument.
+namespace moe {
+constexpr int kStaticHistInts = 65536;                                       // 256 KiB per GPU
+static __device__ __align__(256) int32_t scratch[kStaticHistInts];
+constexpr int kMaxDevices = 64;
+static int32_t* g_scratch_ptr[kMaxDevices];                                  // per device; null until looked up
+static std::mutex g_scratch_mutex;
+
+static moe_status static_scratch_ptr(const char* who, int32_t** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        set_error("%s: hipGetDevice failed or device index %d is outside [0, %d): %s", who, dev, kMaxDevices,
+                  hipGetErrorString(e));
+        return MOE_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_error("%s: hipGetSymbolAddress(scratch) failed on device %d: %s", who, dev, hipGetErrorString(e));
+            return MOE_ERR_DEVICE;
+        }
+        g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+}  // namespace moe
+
+extern "C" size_t moe_permute_static_max_hist_entries(void) { return (size_t)kStaticHistInts; }
+
+extern "C" moe_status moe_permute_static(const moe_shape* s, const void* x, const int32_t* topk_ids, int32_t* counts,
+                                         int32_t* offsets, int32_t* row_of_pair, int32_t* pair_of_row, void* x_perm,
+                                         void* stream) {
+    const char* who = "moe_permute_static";
+    MOE_RETURN_IF(permute_check_args(who, s, x, topk_ids, counts, offsets, row_of_pair, pair_of_row, x_perm));
+    const int64_t need = (int64_t)num_chunks((int64_t)s->T * s->k) * s->E;
+    if (need > kStaticHistInts) {
+        set_error("%s: %lld histogram entries (chunks of the T*k pairs x E) exceed the static scratch of %d entries; "
+                  "use moe_permute with a workspace", who, (long long)need, kStaticHistInts);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    int32_t* hist = nullptr;
+    MOE_RETURN_IF(static_scratch_ptr(who, &hist));
+    return permute_launch(who, s, x, topk_ids, counts, offsets, row_of_pair, pair_of_row, x_perm, hist,
+                          static_cast<hipStream_t>(stream));
 }
 
 extern "C" moe_status moe_permute_lite(const moe_shape* s, int32_t G, int32_t n_rep, const void* x,
