@@ -1,6 +1,6 @@
-// Grouped bf16 GEMM for CDNA4 (gfx950): 256x256x32 workgroup tiles, 8 wavefronts,
+// Grouped bf16 GEMM for CDNA4 (gfx950): 256x256x64 workgroup tiles, 8 wavefronts,
 // MFMA 32x32x16 bf16 with fp32 accumulators, operands streamed HBM -> LDS by the
-// DMA path of the global loads (no register staging) into a ring of four LDS stages.
+// DMA path of the global loads (no register staging) into two LDS stages of 64 KB.
 //
 // One template covers the six products of the expert FFN (paper section 3.1;
 // 6*H*H' FLOPs per routed token forward, backward twice that):
@@ -14,50 +14,39 @@
 //       B  [rows][N]  N contiguous                 (dA|dB, dYp)
 //       C_e [M][N] = sum over the rows of expert e;  an expert without rows gets zeros.
 //
-// An operand tile whose contraction index is contiguous in memory ("row form") is
-// kept in LDS as 256 rows x 64 B and read with ds_read_b128; the 16-byte piece p of
-// row r sits in slot p ^ ((r >> 2) & 3).  An operand tile whose other index is contiguous
-// ("k-row form") is kept as 32 k-rows x 512 B and read with the transposing LDS read
-// (ds_read_b64_tr_b16: lane i of a 16-lane group receives column i of a 4(k) x 16 block);
-// piece p of k-row q sits in slot p ^ (2*(q&3) + 8*(q&1)).  Both swizzles make every LDS
-// read instruction of the main loop conflict-free on the 64 banks.  A DMA load writes
-// 64 lanes x 16 B to consecutive LDS addresses, so the swizzle is applied on the global
-// side: lane l fetches the piece that belongs in slot l.
+// A k-stage is 64 wide.  What the vector memory path charges for is the cache line it touches, not the
+// bytes it delivers (measured per CU for a 32 KB stage from L2: 1300 clocks when every request takes 64 bytes
+// of a line, 770 with whole 128-byte lines, 620 with 512 contiguous bytes - against 1024 clocks of MFMAs
+// for the same stage), so every DMA instruction here asks for whole lines.
 //
-// DUAL: the B tile holds 128 columns of one matrix next to the same 128 columns of a
-// second one (W1|W3 forward, dA|dB wgrad); each wavefront accumulates both products for
-// the same outputs (forward: the epilogue writes silu(a)*b).
+// An operand tile whose contraction index is contiguous in memory ("row form") is kept in LDS as
+// 256 rows x 128 B and read with ds_read_b128; the 16-byte piece p of row r sits in slot
+// p ^ ((r >> 1) & 7).  An operand tile whose other index is contiguous ("k-row form") is kept as
+// 64 k-rows x 512 B and read with the transposing LDS read (ds_read_b64_tr_b16: lane i of a 16-lane
+// group receives column i of a 4(k) x 16 block); piece p of k-row q sits in slot
+// p ^ (2*(q&3) + 8*(q&1)).  Both swizzles make every LDS read instruction of the main loop
+// conflict-free on the 64 banks.  A DMA load writes 64 lanes x 16 B to consecutive LDS addresses, so
+// the swizzle is applied on the global side: lane l fetches the piece that belongs in slot l.
+//
+// DUAL: two B matrices share the A tile (W1|W3 forward, dA|dB wgrad): the B tile holds 128 columns of the
+// first as 64 k-rows x 256 B, then the same 128 columns of the second (same swizzle inside the 16 pieces of
+// a k-row), so that one DMA instruction (4 k-rows x 256 B) reads from one matrix only.  Each wavefront
+// accumulates both products for the same outputs (forward: the epilogue writes silu(a)*b).
 #pragma once
 
 namespace moe {
 
-constexpr int TM = 256, TN = 256, TK = 32;
-constexpr int kStages = 4;
-constexpr int kStageBytes = 32768;  // 16 KB A + 16 KB B
-constexpr int kBOff = 16384;        // B tile inside a stage
-#ifndef MOE_GEMM_WAVES
-#define MOE_GEMM_WAVES 8
-#endif
-// 8 wavefronts (wave tile 128x64, two per SIMD) is the measured optimum: with 4 (wave tile 128x128, a third
-// less LDS read traffic) a single wavefront per SIMD no longer hides its own LDS latency (-20 %).
-constexpr int kWaves = MOE_GEMM_WAVES;
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int kStages = 2;
+constexpr int kStageBytes = 65536;  // 32 KB A + 32 KB B
+constexpr int kBOff = 32768;        // B tile inside a stage
+constexpr int kWaves = 8;           // wave tile 128 x 64, two wavefronts per SIMD
 constexpr int kThreads = kWaves * 64;
 constexpr int kWN = kWaves / 2;            // wavefronts along N (two along M)
 constexpr int NJ = 8 / kWN;                // 32-column MFMA blocks per wavefront
-constexpr int CPW = 16 / kWaves;           // 1 KB DMA chunks per wavefront per operand tile
-#define MOE_STR2(x) #x
-#define MOE_STR(x) MOE_STR2(x)
-#define MOE_VMCNT(n) "s_waitcnt vmcnt(" MOE_STR(n) ")"
-#if MOE_GEMM_WAVES == 4
-#define MOE_VM1 8
-#define MOE_VM2 16
-#define MOE_VM3 24
-#else
-#define MOE_VM1 4
-#define MOE_VM2 8
-#define MOE_VM3 12
-#endif
-constexpr int kGemmLds = kStages * kStageBytes + 2 * (MOE_MAX_EXPERTS + 1) * 4 + 16;  // ring + expert table + 2 draw slots
+constexpr int CPW = 32 / kWaves;           // 1 KB DMA chunks per wavefront per operand tile
+constexpr int kSteps = TK / 16;            // MFMA k-steps per stage
+constexpr int kGemmLds = kStages * kStageBytes + 2 * (MOE_MAX_EXPERTS + 1) * 4 + 16;  // stages + expert table + 2 draw slots
 // Tile queues (GArgs::sched): one counter per XCD, kSchedStride words apart, all zero when the kernel starts.
 constexpr int kSchedStride = 32;
 constexpr int kSchedWords = 8 * kSchedStride;
@@ -70,11 +59,12 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define LDS_AS __attribute__((address_space(3)))
 
 
-// Scheduling pattern for one k-step: MFMA, LDS read, MFMA, LDS read, ... then a fence.
-template <int N>
+// Scheduling pattern for one k-step: MFMA, LDS read, MFMA, LDS read, ... (as many pairs as there are
+// MFMAs or reads, whichever is more), then a fence.
+template <int kMfma, int kReads>
 __device__ __forceinline__ void interleave_mfma_dsread() {
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
+    for (int i = 0; i < (kMfma > kReads ? kMfma : kReads); ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
     }
@@ -82,7 +72,7 @@ __device__ __forceinline__ void interleave_mfma_dsread() {
 }
 
 // slot = piece ^ swz: chosen so that the rows one LDS read instruction touches fall into different banks
-__device__ __forceinline__ int swz_rows(int row) { return (row >> 2) & 3; }              // 64-byte rows, b128 reads
+__device__ __forceinline__ int swz_rows(int row) { return (row >> 1) & 7; }              // 128-byte rows, b128 reads
 __device__ __forceinline__ int swz_krow(int q) { return 2 * (q & 3) + 8 * (q & 1); }      // 512-byte k-rows, tr reads
 
 // 16 bytes per lane, global -> LDS, without passing through registers: lane l lands at
@@ -157,6 +147,7 @@ struct TileDesc {
 template <int AT, int BT, bool DUAL, int EPI, bool RAGK>
 __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     static_assert(RAGK ? (AT == 1 && BT == 0) : (AT == 0), "operand forms");
+    static_assert(!(DUAL && BT == 1), "two B matrices are taken in k-row form only");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     int32_t* t_off = reinterpret_cast<int32_t*>(smem + kStages * kStageBytes);  // [E+1] rows of each expert
     int32_t* t_pref = t_off + MOE_MAX_EXPERTS + 1;                              // [E+1] tiles before expert e
@@ -199,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     // tiles are cut into their upper and lower 128 rows (logical tiles split_from + 2i and + 2i + 1), so that
     // the round costs a 128-row tile's time instead of a full one's.
     int total_tiles = t_pref[g.E], split_from = total_tiles;
-    if constexpr (!RAGK && kWaves == 8) {
+    if constexpr (!RAGK) {
         const int left = total_tiles % (int)gridDim.x;
         if (g.sched == nullptr && left > 0 && 2 * left <= (int)gridDim.x) {
             split_from = total_tiles - left;
@@ -290,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
         }
         t.n0 = nt * n_out;
-        t.nk = (t.kend - t.kbeg + TK - 1) / TK;  // exact when M is ragged (K % 32 == 0)
+        t.nk = (t.kend - t.kbeg + TK - 1) / TK;  // exact when M is ragged (K % 64 == 0)
         if (!RAGK && t.m0 >= t.m_lim) t.nk = 0;   // the lower half of a tile of at most 128 rows: nothing to do
         t.e = __builtin_amdgcn_readfirstlane(t.e);
         t.m0 = __builtin_amdgcn_readfirstlane(t.m0);
@@ -299,7 +290,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         t.kbeg = __builtin_amdgcn_readfirstlane(t.kbeg);
         t.kend = __builtin_amdgcn_readfirstlane(t.kend);
         t.nk = __builtin_amdgcn_readfirstlane(t.nk);
-        if constexpr (!RAGK && kWaves == 8) t.half = t.m_lim - t.m0 <= TM / 2;
+        if constexpr (!RAGK) t.half = t.m_lim - t.m0 <= TM / 2;
         return t;
     };
 
@@ -307,24 +298,30 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     const int64_t lda = g.lda, ldb = g.ldb;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * (CPW * 1024));
-    // row form: chunk c = wave*2 + i covers rows 16c .. 16c+15; lane -> row 16c + lane/4, slot lane%4
+    // row form: chunk c = wave*CPW + i covers rows 8c .. 8c+7; lane -> row 8c + lane/8, slot lane%8
     // k-row form: chunk c covers k-rows 2c, 2c+1; lane -> k-row 2c + lane/32, slot lane%32
+    // k-row form, two matrices: chunk c covers k-rows 4(c%16) .. +3 of matrix c/16 (wavefronts 0-3 load the
+    //   first matrix, 4-7 the second); lane -> k-row 4(c%16) + lane/16, slot lane%16
     TileDesc di;                  // tile whose stages are being issued
     di.valid = false; di.half = false; di.e = 0; di.m0 = 0; di.m_lim = 0; di.n0 = 0; di.kbeg = 0; di.kend = 0; di.nk = 0;
     // Ragged M: per-lane byte offsets of this lane's 16-byte pieces relative to a wave-uniform base of the tile
-    // (sA / sB per K segment; pB for the two-matrix B tile, whose lanes read from two allocations).
-    // Ragged K: element offsets (k-independent part), full addresses are formed per load.
+    // (sA / sB per K segment; with two B matrices sB is the base of the matrix this wavefront loads).
+    // Ragged K: byte offsets relative to the first k-row of the stage (the base moves by scalar adds); only a
+    // stage that reaches past the expert's last row forms full per-lane addresses.
+    constexpr bool kBDual = DUAL && BT == 0;   // the B tile is two half-width k-row tiles
+    const int b_mat = kBDual ? __builtin_amdgcn_readfirstlane(wave >> 2) : 0;  // the matrix this wavefront's B chunks come from
     uint32_t a_off[CPW], b_off[CPW];
     const char* sA[2];
     const char* sB[2];
-    const bf16_t* pB[2][CPW];
-    bool b_second[CPW];
     const bf16_t* iA[2];
-    const bf16_t* iB[2];
-    const bf16_t* iB2[2];
-    int q_row[CPW];  // k-row form: the k-row inside the stage of this lane's piece in chunk i
+    const bf16_t* iB[2];   // ragged K: the matrix this wavefront's B chunks come from
+    int qa_row[CPW], qb_row[CPW];  // k-row form: the k-row inside the stage of this lane's piece in chunk i
 #pragma unroll
-    for (int i = 0; i < CPW; ++i) { q_row[i] = (wave * CPW + i) * 2 + (lane >> 5); b_second[i] = false; }
+    for (int i = 0; i < CPW; ++i) {
+        const int c = wave * CPW + i;
+        qa_row[i] = c * 2 + (lane >> 5);
+        qb_row[i] = kBDual ? (c & 15) * 4 + (lane >> 4) : c * 2 + (lane >> 5);
+    }
 
     auto setup_issue = [&]() {
 #pragma unroll
@@ -332,8 +329,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             const int q = sgi < g.nseg ? sgi : 0;
             const int64_t eoff = RAGK ? 0 : (int64_t)weight_index(g, di.e) * g.strideB;
             iA[sgi] = static_cast<const bf16_t*>(g.seg[q].A);
-            iB[sgi] = static_cast<const bf16_t*>(g.seg[q].B) + eoff;
-            iB2[sgi] = DUAL ? static_cast<const bf16_t*>(g.seg[q].B2) + eoff : nullptr;
+            iB[sgi] = static_cast<const bf16_t*>(kBDual && b_mat ? g.seg[q].B2 : g.seg[q].B) + eoff;
         }
 #pragma unroll
         for (int sgi = 0; sgi < 2; ++sgi) {
@@ -345,40 +341,31 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         for (int i = 0; i < CPW; ++i) {
             const int c = wave * CPW + i;
             if constexpr (AT == 0) {
-                const int r = c * 16 + (lane >> 2);
+                const int r = c * 8 + (lane >> 3);
                 const int last = di.m_lim - 1 - di.m0;  // rows past the expert's end: any valid row (masked at the store)
                 const int rl = r < last ? r : last;
-                a_off[i] = ((uint32_t)rl * (uint32_t)lda + ((lane & 3) ^ swz_rows(r)) * 8) * 2;
+                a_off[i] = ((uint32_t)rl * (uint32_t)lda + ((lane & 7) ^ swz_rows(r)) * 8) * 2;
             } else {
-                int col = di.m0 + ((lane & 31) ^ swz_krow(q_row[i])) * 8;
+                int col = di.m0 + ((lane & 31) ^ swz_krow(qa_row[i])) * 8;
                 col = col < g.M ? col : g.M - 8;
-                a_off[i] = col;
+                a_off[i] = ((uint32_t)qa_row[i] * (uint32_t)lda + (uint32_t)col) * 2;
             }
             if constexpr (BT == 1) {
-                const int r = c * 16 + (lane >> 2);
+                const int r = c * 8 + (lane >> 3);
                 const int last = g.N - 1 - di.n0;
                 const int rl = r < last ? r : last;
-                b_off[i] = ((uint32_t)rl * (uint32_t)ldb + ((lane & 3) ^ swz_rows(r)) * 8) * 2;
+                b_off[i] = ((uint32_t)rl * (uint32_t)ldb + ((lane & 7) ^ swz_rows(r)) * 8) * 2;
             } else {
-                const int piece = (lane & 31) ^ swz_krow(q_row[i]);
                 int col;
-                if constexpr (DUAL) col = di.n0 + (piece & 15) * 8;  // pieces 16..31 come from the second matrix
-                else col = di.n0 + piece * 8;
+                if constexpr (kBDual) col = di.n0 + ((lane & 15) ^ swz_krow(qb_row[i])) * 8;
+                else col = di.n0 + ((lane & 31) ^ swz_krow(qb_row[i])) * 8;
                 col = col < g.N ? col : g.N - 8;
-                if constexpr (RAGK) {
-                    b_off[i] = col;
-                    if constexpr (DUAL) b_second[i] = (piece >> 4) != 0;
-                } else if constexpr (DUAL) {
-#pragma unroll
-                    for (int sgi = 0; sgi < 2; ++sgi)
-                        pB[sgi][i] = ((piece >> 4) != 0 ? iB2[sgi] : iB[sgi]) + (int64_t)q_row[i] * ldb + col;
-                } else {
-                    b_off[i] = ((uint32_t)q_row[i] * (uint32_t)ldb + (uint32_t)(col - di.n0)) * 2;
-                }
+                if constexpr (RAGK) b_off[i] = ((uint32_t)qb_row[i] * (uint32_t)ldb + (uint32_t)col) * 2;
+                else b_off[i] = ((uint32_t)qb_row[i] * (uint32_t)ldb + (uint32_t)(col - di.n0)) * 2;
             }
         }
     };
-    // k-stage `stage` of tile di -> ring buffer `buf`: always exactly 2*CPW DMA instructions per wavefront,
+    // k-stage `stage` of tile di -> stage buffer `buf`: always exactly 2*CPW DMA instructions per wavefront,
     // numbered idx = 0 .. 2*CPW-1 (A chunks first); issue_part issues the idx range [lo, hi).
     auto issue_part = [&](int stage, int buf, int lo, int hi) {
         const int sg = stage >= di.nk ? 1 : 0;
@@ -395,29 +382,39 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
                 if (CPW + i < lo || CPW + i >= hi) continue;
-                if constexpr (BT == 0 && DUAL) dma16((sg ? pB[1][i] : pB[0][i]) + (int64_t)k0 * ldb, st + kBOff + i * 1024);
-                else dma16_s(Bb, b_off[i], st + kBOff + i * 1024);
+                dma16_s(Bb, b_off[i], st + kBOff + i * 1024);
             }
         } else {
-            const bf16_t* A = sg ? iA[1] : iA[0];
-            const bf16_t* B = sg ? iB[1] : iB[0];
+            const char* Ab = reinterpret_cast<const char*>(sg ? iA[1] : iA[0]) + (int64_t)k0 * lda * 2;
+            const char* Bb = reinterpret_cast<const char*>(sg ? iB[1] : iB[0]) + (int64_t)k0 * ldb * 2;
+            if (k0 + TK <= di.kend) {  // (wave-uniform) every k-row of the stage belongs to the expert
 #pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                if (i < lo || i >= hi) continue;
-                // k-rows past the expert's rows read a row of zeros: they add nothing to the sums
-                const int kr = k0 + q_row[i];
-                const bf16_t* src = kr < di.kend ? A + (int64_t)kr * lda + a_off[i]
-                                                 : static_cast<const bf16_t*>(g.zero_row) + (lane & 31) * 8;
-                dma16(src, st + i * 1024);
-            }
+                for (int i = 0; i < CPW; ++i) {
+                    if (i < lo || i >= hi) continue;
+                    dma16_s(Ab, a_off[i], st + i * 1024);
+                }
 #pragma unroll
-            for (int i = 0; i < CPW; ++i) {
-                if (CPW + i < lo || CPW + i >= hi) continue;
-                int kr = k0 + q_row[i];
-                kr = kr < di.kend ? kr : di.kend - 1;  // any valid (finite) row: it meets zeros
-                const bf16_t* src = B;
-                if constexpr (DUAL) src = b_second[i] ? (sg ? iB2[1] : iB2[0]) : B;
-                dma16(src + (int64_t)kr * ldb + b_off[i], st + kBOff + i * 1024);
+                for (int i = 0; i < CPW; ++i) {
+                    if (CPW + i < lo || CPW + i >= hi) continue;
+                    dma16_s(Bb, b_off[i], st + kBOff + i * 1024);
+                }
+            } else {
+                const int left = di.kend - k0;  // k-rows of the stage that exist, 1 .. TK-1
+#pragma unroll
+                for (int i = 0; i < CPW; ++i) {
+                    if (i < lo || i >= hi) continue;
+                    // k-rows past the expert's rows read a row of zeros: they add nothing to the sums
+                    const char* src = qa_row[i] < left ? Ab + a_off[i]
+                                                       : static_cast<const char*>(g.zero_row) + (lane & 31) * 16;
+                    dma16(src, st + i * 1024);
+                }
+#pragma unroll
+                for (int i = 0; i < CPW; ++i) {
+                    if (CPW + i < lo || CPW + i >= hi) continue;
+                    // any valid (finite) row: it meets zeros
+                    const int over = qb_row[i] < left ? 0 : qb_row[i] - (left - 1);
+                    dma16(Bb + (b_off[i] - (uint32_t)over * (uint32_t)ldb * 2), st + kBOff + i * 1024);
+                }
             }
         }
     };
@@ -431,11 +428,12 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     const int tr_krow = (g16 >> 1) * 8 + (i16 >> 2);  // + kk*16 + t*4
     const int tr_sw = swz_krow(tr_krow);              // kk*16 + t*4 do not change the swizzle
     const int tr_lane_col = (g16 & 1) * 16 + (i16 & 3) * 4;
+    constexpr int kBRow = kBDual ? 256 : 512;         // bytes per k-row of the B tile
     int a_rd[4], b_rd[NJ];  // byte offsets inside the operand tile, without the k-step term
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if constexpr (AT == 0) {
-            a_rd[i] = (wm * 128 + i * 32 + l32) * 64;
+            a_rd[i] = (wm * 128 + i * 32 + l32) * 128;
         } else {
             const int col = wm * 128 + i * 32 + tr_lane_col;
             a_rd[i] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
@@ -443,32 +441,35 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     }
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-        // DUAL: blocks j < NJ/2 lie in the first matrix' half of the B tile, the others in the second
-        const int cb = DUAL ? ((j / (NJ / 2)) * 128 + wn * (NJ / 2) * 32 + (j % (NJ / 2)) * 32) : (wn * NJ * 32 + j * 32);
         if constexpr (BT == 1) {
-            b_rd[j] = (cb + l32) * 64;
+            // DUAL with row-form B does not occur (the two-matrix products have their weights in k-row form)
+            b_rd[j] = (wn * NJ * 32 + j * 32 + l32) * 128;
+        } else if constexpr (kBDual) {
+            // blocks j < NJ/2 lie in the first matrix' half of the B tile, the others in the second
+            const int col = wn * (NJ / 2) * 32 + (j % (NJ / 2)) * 32 + tr_lane_col;
+            b_rd[j] = (j / (NJ / 2)) * (kBOff / 2) + tr_krow * 256 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
         } else {
-            const int col = cb + tr_lane_col;
+            const int col = wn * NJ * 32 + j * 32 + tr_lane_col;
             b_rd[j] = tr_krow * 512 + (((col >> 3) ^ tr_sw) << 4) + (col & 7) * 2;
         }
     }
-    // fragments of k-step kk of a stage -> registers.  B first: the MFMAs below walk a[0] x b[0..1],
-    // a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
+    // fragments of k-step kk (0 .. kSteps-1) of a stage -> registers.  B first: the MFMAs below walk
+    // a[0] x b[0..1], a[1] x b[0..1], ..., so the operands requested last are the ones needed last.
     // NI = row blocks per wavefront: 4 (128 x 64 per wavefront, 256-row tile) or 2 (64 x 64, 128-row tile:
-    // wavefront row wm then starts at row 64*wm, which `a_shift` = wm*64 rows takes off the A offsets).
+    // wavefront row wm then starts at row 64*wm, which is taken off the A offsets).
     auto load_frags = [&](auto ni_tag, const char* st, int kk, bf16x8 (&a)[4], bf16x8 (&b)[NJ]) {
         constexpr int NI = decltype(ni_tag)::value;
         const char* sb = st + kBOff;
-        if constexpr (NI == 2 && AT == 0) st -= wm * 64 * 64;
+        if constexpr (NI == 2 && AT == 0) st -= wm * 64 * 128;
         const int rowform = ((kk * 2 + kg) ^ a_sw) << 4;
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             if constexpr (BT == 1) {
                 b[j] = *reinterpret_cast<const bf16x8*>(sb + b_rd[j] + rowform);
             } else {
-                const char* p = sb + b_rd[j] + kk * 8192;
+                const char* p = sb + b_rd[j] + kk * (16 * kBRow);
                 const bf16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p);
-                const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 2048));
+                const bf16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p + 4 * kBRow));
                 b[j] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
@@ -505,8 +506,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     // the waits and the barrier that follow (instruction selection otherwise moves most of a k-step's
     // MFMAs behind the barrier, which then drains the matrix pipe while the wavefronts wait).
     auto pin_one = [](f32x16& v) {
-        if constexpr (kWaves == 8) asm volatile("" : "+v"(v));  // 256 registers per lane: all of them VGPRs
-        else asm volatile("" : "+a"(v));                        // 512: accumulators in AGPRs
+        asm volatile("" : "+v"(v));
     };
     auto pin_acc = [&](auto ni_tag) {
         constexpr int NI = decltype(ni_tag)::value;
@@ -518,8 +518,8 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
 
     // ---- epilogue of one tile.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
     // inside a 32x32 block) go through LDS, 64 rows at a time (block i of both wavefront rows), so that
-    // global memory sees 16-byte accesses along rows.  `stg` is the last 32 KB ring buffer; the bf16 epilogues
-    // also use the one in front of it, the first kPreStages buffers hold the next tile's first stages.
+    // global memory sees 16-byte accesses along rows.  `stg` is the second stage buffer (64 KB: two staging
+    // areas of 32 KB); the first one already receives the next tile's first stage.
     auto epilogue_zero = [&](const TileDesc& t) {  // ragged K, expert without rows: exact zeros, no staging needed
         const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
         {
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     auto epilogue = [&](const TileDesc& t, char* stg) {
         const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
         // a 128-row tile holds two row blocks per wavefront, the rows of wavefront row 1 start at 64
-        const bool half = !RAGK && kWaves == 8 && t.half;
+        const bool half = !RAGK && t.half;
         const int ni = half ? 2 : 4, wrows = half ? 64 : 128;
         if constexpr (EPI == EPI_STORE_F32) {  // narrow fp32 output (gate weight gradient): direct stores
 #pragma unroll
@@ -664,7 +664,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
         } else {
             // bf16 tiles: stage [64 rows][ROWB bytes] with swizzled 16-byte pieces, then 16 bytes per lane along rows.
-            // Two staging buffers (ring buffers 2 and 3; 0 and 1 hold the next tile's first stages) take the
+            // Two staging areas (the halves of the second stage buffer) take the
             // passes in turn, so one barrier per pass is enough: a wavefront that writes pass p+2 has passed the
             // barrier of pass p+1, which every wavefront reaches only after it has read pass p.
             constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
@@ -711,7 +711,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                 }
             };
             int pn = 0;  // passes so far
-            auto next_buf = [&]() { return stg - ((pn++ & 1) ? 0 : kStageBytes); };  // ring buffers 2, 3, 2, ...
+            auto next_buf = [&]() { return stg + ((pn++ & 1) ? kStageBytes / 2 : 0); };  // the two areas in turn
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (i >= ni) break;
@@ -758,20 +758,16 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                     flush(sb, i, static_cast<bf16_t*>(g.C0), nullptr, 0);
                 }
             }
-            __syncthreads();  // the last two passes have been read: both staging buffers may take the next tile's stages
+            __syncthreads();  // the last two passes have been read: the buffer may take the next tile's second stage
         }
     };
 
     // ================= the tiles of this workgroup =================
-    // Per tile: stages 0..3 are in flight when its loop starts (the first kPreStages of them were issued
-    // before the previous tile's epilogue, the others after it); the barrier in the middle of iteration `it`
-    // publishes stage it+1 and frees the buffer of stage it, into which stage it+4 is issued at once.
+    // Per tile: stages 0 and 1 are in flight when its loop starts (stage 0 was requested before the previous
+    // tile's epilogue, stage 1 after it).  Iteration `it` runs the four k-steps of stage `it`; the barrier in
+    // front of the last k-step publishes stage it+1 and frees the buffer of stage it, into which stage it+2 is
+    // requested at once: a stage has one whole iteration (about 2 us) to land.
     bf16x8 fa[2][4], fb[2][NJ];
-    auto wait_loads = [&](int stages_allowed) {  // at most that many of the youngest stage loads may be pending
-        if (stages_allowed >= 2) asm volatile(MOE_VMCNT(MOE_VM2) ::: "memory");
-        else if (stages_allowed == 1) asm volatile(MOE_VMCNT(MOE_VM1) ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    };
     int round = 0;
     auto static_tile = [&]() { return logical_tile(blockIdx.x + round++ * gridDim.x); };
     TileDesc t = decode(dyn ? draw_now(false) : static_tile());
@@ -791,27 +787,33 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     auto run_tile = [&](auto ni_tag, const int total, const int ahead) {
         constexpr int NI = decltype(ni_tag)::value;
         constexpr int kReads = (AT == 0 ? NI : 2 * NI) + (BT == 1 ? NJ : 2 * NJ);
-        constexpr int kPairs = kReads > NI * NJ ? kReads : NI * NJ;  // MFMA / LDS-read pairs to interleave per k-step
         constexpr int kDeal = 2 * CPW / NI;                         // DMA instructions behind each row of MFMAs
-        // stage 0 must have landed: it is followed by min(total, 4) - 1 younger stage loads
-        if (total >= 4) asm volatile(MOE_VMCNT(MOE_VM3) ::: "memory");
-        else wait_loads(total - 1);
+        // stage 0 must have landed: behind it at most the 2*CPW loads of stage 1 are pending
+        if (total >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * CPW) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         load_frags(ni_tag, smem, 0, fa[0], fb[0]);
+        // k-steps 0 .. kSteps-2 of a stage: the fragments of the next k-step are read while the MFMAs of this one issue
+        auto steps_before_barrier = [&](const char* st) {
+#pragma unroll
+            for (int kk = 0; kk < kSteps - 1; ++kk) {
+                load_frags(ni_tag, st, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+                mma(ni_tag, fa[kk & 1], fb[kk & 1]);
+                interleave_mfma_dsread<NI * NJ, kReads>();
+            }
+            pin_acc(ni_tag);
+        };
         int it = 0;
         // ---- hot loop: branch-free ----
         for (; it + kStages < total; ++it) {
-            const char* st = smem + (it & (kStages - 1)) * kStageBytes;
-            const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
-            load_frags(ni_tag, st, 1, fa[1], fb[1]);
-            mma(ni_tag, fa[0], fb[0]);
-            interleave_mfma_dsread<kPairs>();
-            pin_acc(ni_tag);
-            // this wavefront's reads of stage `it` have returned; its share of stage it+1 has landed
-            // (the youngest 4*CPW loads belong to stages it+2 and it+3)
-            asm volatile(MOE_VMCNT(MOE_VM2) " lgkmcnt(0)" ::: "memory");
+            const char* st = smem + (it & 1) * kStageBytes;
+            const char* nx = smem + ((it + 1) & 1) * kStageBytes;
+            steps_before_barrier(st);
+            // this wavefront's reads of stage `it` have returned and its share of stage it+1 has landed
+            // (nothing else is in flight: stage it+2 is requested below)
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             __syncthreads();
-            // second k-step: the DMA instructions of stage it+4 (and their address arithmetic) are dealt out
+            // last k-step: the DMA instructions of stage it+2 (and their address arithmetic) are dealt out
             // between the MFMAs, an equal share after each row of MFMA blocks, so that the matrix pipe stays
             // fed while they issue; the pins keep each row of MFMAs in front of its share.
             load_frags(ni_tag, nx, 0, fa[0], fb[0]);
@@ -822,43 +824,41 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
                     pin_one(acc[i][j]);
                 }
-                issue_part(it + kStages, it & (kStages - 1), i * kDeal, (i + 1) * kDeal);
+                issue_part(it + kStages, it & 1, i * kDeal, (i + 1) * kDeal);
                 if (i < NI - 1) pin_one(acc[i + 1][0]);  // the next row's MFMAs read this value: they stay behind the DMA
             }
         }
-        // ---- the last (up to four) stages: nothing left to issue for this tile ----
+        // ---- the last (up to two) stages: nothing left to issue for this tile ----
         for (; it < total; ++it) {
-            const char* st = smem + (it & (kStages - 1)) * kStageBytes;
-            const char* nx = smem + ((it + 1) & (kStages - 1)) * kStageBytes;
-            load_frags(ni_tag, st, 1, fa[1], fb[1]);
-            mma(ni_tag, fa[0], fb[0]);
-            interleave_mfma_dsread<kPairs>();
+            const char* st = smem + (it & 1) * kStageBytes;
+            const char* nx = smem + ((it + 1) & 1) * kStageBytes;
+            steps_before_barrier(st);
             const int rem = total - 1 - it;  // stages after this one, all issued already
-            pin_acc(ni_tag);
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            wait_loads(rem - 1);
-            if (rem == 0 && threadIdx.x == 0) s_draw[1] = ahead;  // (rem == 0: every load of this wavefront has returned)
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            if (rem == 0 && threadIdx.x == 0) s_draw[1] = ahead;  // (every load of this wavefront has returned)
             __syncthreads();
             if (rem > 0) load_frags(ni_tag, nx, 0, fa[0], fb[0]);
             mma(ni_tag, fa[1], fb[1]);
-            interleave_mfma_dsread<kPairs>();
+            interleave_mfma_dsread<NI * NJ, kReads>();
         }
     };
-    // Stages of the next tile requested before this tile's epilogue; the epilogue stages through the other ring buffers.
-    constexpr int kPreStages = (EPI == EPI_STORE || EPI == EPI_STORE2 || EPI == EPI_SWIGLU) ? kStages - 2 : kStages - 1;
+    // Stage 0 of the next tile is requested before this tile's epilogue; the epilogue stages through the other buffer.
+    constexpr int kPreStages = 1;
     for (;;) {
         const int total = t.nk * g.nseg;
         zero_acc();
         // The draw for the next tile, as inline assembly: the compiler would wait for the returned value on
         // the spot (it broadcasts it inside the wavefront), which stalls the first stages of the tile behind
         // the round trip.  Like the DMA loads, this one is waited for by the loop's own vmcnt waits; the
-        // value is first read behind the vmcnt(0) of the tile's last stage.
+        // value is first read behind the vmcnt(0) of the tile's last stage.  The register is tied in and out
+        // ("+v"), so the value the asm statement defines is the one the later store reads: no copy of it can
+        // be made before the wait.
         int ahead = 0;
         if (dyn && threadIdx.x == 0) {
             const uint32_t one = 1u;
-            asm volatile("global_atomic_add %0, %1, %2, off sc0" : "=v"(ahead) : "v"(queue_counter()), "v"(one) : "memory");
+            asm volatile("global_atomic_add %0, %1, %2, off sc0" : "+v"(ahead) : "v"(queue_counter()), "v"(one) : "memory");
         }
-        if constexpr (!RAGK && kWaves == 8) {
+        if constexpr (!RAGK) {
             if (t.half) run_tile(IntTag<2>{}, total, ahead);
             else run_tile(IntTag<4>{}, total, ahead);
         } else {
@@ -867,9 +867,9 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         // Nothing is outstanding here (the loop ended with vmcnt(0)); said with the builtin so that the
         // compiler's own bookkeeping agrees and no load counts as pending in the next tile's loop.
         __builtin_amdgcn_s_waitcnt(0x0F70);
-        // ---- next tile: its first stages are requested before this tile's epilogue ----
+        // ---- next tile: its first stage is requested before this tile's epilogue ----
         // (every DMA load of this tile has landed and every wavefront is past the last barrier, after
-        // which nobody reads LDS any more: all four buffers are free)
+        // which nobody reads LDS any more: both buffers are free)
         auto next_tile = [&](bool first) -> int {
             if (!dyn) return static_tile();
             if (first) {  // the draw made ahead; from an empty queue it is void, like every later draw from it
@@ -893,7 +893,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             ntot = nt.nk * g.nseg;
             for (int sq = 0; sq < kPreStages && sq < ntot; ++sq) issue(sq, sq);
         }
-        epilogue(t, smem + (kStages - 1) * kStageBytes);
+        epilogue(t, smem + kStageBytes);
         if (!nt.valid) break;
         for (int sq = kPreStages; sq < kStages && sq < ntot; ++sq) issue(sq, sq);
         t = nt;

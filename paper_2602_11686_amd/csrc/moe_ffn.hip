@@ -15,11 +15,11 @@
 //   dgrad 2     dXp_e = dA_e * W1_e^T + dB_e * W3_e^T      (two K segments)
 //   wgrad       dW2_e = H_e^T * dYp_e,  [dW1_e|dW3_e] = Xp_e^T * [dA_e|dB_e]
 //
-// bf16 path: the persistent 256x256x32 kernel of grouped_gemm_bf16.h (8 wavefronts,
+// bf16 path: the persistent 256x256x64 kernel of grouped_gemm_bf16.h (8 wavefronts,
 // MFMA 32x32x16 bf16 with fp32 accumulators, operands brought into LDS by DMA in
 // memory order, transposing LDS reads where the contraction index is not the
 // contiguous one).  Shapes it does not take (leading dimensions that are not a
-// multiple of 8, K not a multiple of 32) run on the plain 128x128x64 kernel below.
+// multiple of 8, K not a multiple of 64) run on the plain 128x128x64 kernel below.
 // fp32 path (parity mode): plain FMA tiles, same tile walk and epilogues.
 #include "moe_internal.h"
 

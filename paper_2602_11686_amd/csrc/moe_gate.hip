@@ -464,7 +464,7 @@ static inline int mma_chunk_tokens(int Tn) {
     return need <= 512 ? 512 : (need + 31) / 32 * 32;
 }
 static inline int mma_chunks(int Tn) { const int c = mma_chunk_tokens(Tn); return (Tn + c - 1) / c; }
-static inline int pad32(int v) { return (v + 31) / 32 * 32; }  // the dense dL is a K operand: whole 32-wide k-stages
+static inline int pad64(int v) { return (v + 63) / 64 * 64; }  // the dense dL is a K operand: whole 64-wide k-stages
 
 // one wavefront per token: dl[t,s] (fp32, for the dx update) and the dense hi/lo rows
 __global__ __launch_bounds__(256) void gate_dl_dense_kernel(const int32_t* __restrict__ ids, const float* __restrict__ w,
@@ -528,12 +528,12 @@ __global__ void gate_bwd_dwg_reduce_mma_kernel(const float* __restrict__ partial
 }
 
 size_t gate_bwd_workspace_bytes(const moe_shape* s) {
-    size_t b = align_up((size_t)pad32(s->E) * s->d * 4, 256);          // wgT (fp32), or the padded bf16 gate weight
+    size_t b = align_up((size_t)pad64(s->E) * s->d * 4, 256);          // wgT (fp32), or the padded bf16 gate weight
     b += align_up((size_t)s->T * s->k * 4, 256);                       // dl
     const size_t p_valu = (size_t)dwg_chunks(s->T) * s->E * s->d * 4;
-    const size_t p_mma = (size_t)mma_chunks(s->T) * s->d * pad32(s->E) * 4;
+    const size_t p_mma = (size_t)mma_chunks(s->T) * s->d * pad64(s->E) * 4;
     b += align_up(p_valu > p_mma ? p_valu : p_mma, 256);               // partial sums
-    b += 2 * align_up((size_t)s->T * pad32(s->E) * 2, 256);             // dense dL, hi and lo
+    b += 2 * align_up((size_t)s->T * pad64(s->E) * 2, 256);             // dense dL, hi and lo
     b += align_up((size_t)(mma_chunks(s->T) + 1) * 4, 256) + 512 + 256;  // token chunk offsets, a row of zeros, {0, T}
     return b;
 }
@@ -605,15 +605,15 @@ template <class T>
 static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gate, const int32_t* ids,
                                   const float* w, const float* dw, T* dx, float* dwg, void* ws, hipStream_t st) {
     Carver cv(ws);
-    float* wgT = static_cast<float*>(cv.take((size_t)pad32(s->E) * s->d * 4));  // fp32 transpose, or the padded bf16 copy
+    float* wgT = static_cast<float*>(cv.take((size_t)pad64(s->E) * s->d * 4));  // fp32 transpose, or the padded bf16 copy
     float* dl = static_cast<float*>(cv.take((size_t)s->T * s->k * 4));
     const int nchunks = dwg_chunks(s->T);
     const size_t p_valu = (size_t)nchunks * s->E * s->d * 4;
-    const size_t p_mma = (size_t)mma_chunks(s->T) * s->d * pad32(s->E) * 4;
+    const size_t p_mma = (size_t)mma_chunks(s->T) * s->d * pad64(s->E) * 4;
     float* partial = static_cast<float*>(cv.take(p_valu > p_mma ? p_valu : p_mma));
     const bool mma = sizeof(T) == 2 && s->d % 8 == 0;
     if (mma) {
-        const int n_pad = pad32(s->E), nch = mma_chunks(s->T);
+        const int n_pad = pad64(s->E), nch = mma_chunks(s->T);
         bf16_t* hi = static_cast<bf16_t*>(cv.take((size_t)s->T * n_pad * 2));
         bf16_t* lo = static_cast<bf16_t*>(cv.take((size_t)s->T * n_pad * 2));
         int32_t* coff = static_cast<int32_t*>(cv.take((size_t)(nch + 1) * 4));

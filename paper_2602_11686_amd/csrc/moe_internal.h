@@ -46,7 +46,7 @@ void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, c
 
 // dx += (dl_hi + dl_lo) * wg_pad^T on the matrix cores (implemented next to the grouped GEMM):
 // dl_hi / dl_lo [T][n_pad] bf16, wg_pad [d][n_pad] bf16 (gate weight, columns past E zero), n_pad a multiple
-// of 32, whole = {0, T} in device memory, dx [T][d] bf16 read and written.
+// of 64, whole = {0, T} in device memory, dx [T][d] bf16 read and written.
 void launch_gate_dx_gemm(const void* dl_hi, const void* dl_lo, const void* wg_pad, const int32_t* whole, int d, int n_pad,
                          void* dx, hipStream_t st);
 

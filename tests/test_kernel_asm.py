@@ -63,11 +63,50 @@ def test_main_loops_hold_only_the_hand_placed_vmcnt_waits(ffn_asm):
             if mfma < 8 or not any("s_barrier" in i for i in ins):
                 continue  # not a main-loop block (a stage = MFMAs around one barrier)
             seen_loops += 1
-            waits = [int(re.search(r"vmcnt\((\d+)\)", i).group(1)) for i in ins
+            waits = [(n, int(re.search(r"vmcnt\((\d+)\)", i).group(1))) for n, i in enumerate(ins)
                      if i.startswith("s_waitcnt") and "vmcnt" in i]
-            # the one wait of a stage lets the two youngest stages (8 DMA loads per wavefront) stay in flight
-            assert waits == [8], f"{name} {label}: vmcnt waits {waits} inside a main-loop stage"
+            # the one wait of a stage sits right in front of its barrier: the next stage has landed, and since
+            # the stage after it is requested only behind the barrier, nothing else is in flight
+            assert [w for _, w in waits] == [0], f"{name} {label}: vmcnt waits {waits} inside a main-loop stage"
+            bar = next(n for n, i in enumerate(ins) if "s_barrier" in i)
+            between = [i for i in ins[waits[0][0] + 1:bar] if i.startswith(("ds_read", "global_load", "buffer_load"))]
+            assert 0 < bar - waits[0][0] and not between, f"{name} {label}: the wait is not the one in front of the barrier"
     assert seen_loops >= len(ks)
+
+
+def test_look_ahead_draw_is_first_read_behind_a_full_wait(ffn_asm):
+    """The queue draw for the next tile is a returning atomic issued from inline assembly; its result arrives
+    asynchronously.  The only reader of the destination register must be the LDS store that publishes it, and
+    that store must follow an s_waitcnt vmcnt(0) in its own straight-line code."""
+    found = 0
+    for m in re.finditer(r"^(_ZN3moe12gg256_kernel\w+Lb1EEEvNS_5GArgsE):(.*?)\n\s*s_endpgm", ffn_asm, re.S | re.M):
+        lines = [l.strip() for l in m.group(2).split("\n")]
+        lines = [l for l in lines if l and not l.startswith(";") and (not l.startswith(".") or l.startswith(".LBB"))]
+        for n, l in enumerate(lines):
+            a = re.match(r"global_atomic_add (v\d+), v\[\d+:\d+\], v\d+, off sc0", l)
+            if not a:
+                continue
+            found += 1
+            reg = a.group(1)
+            word = re.compile(r"\b%s\b" % reg)
+            readers = []
+            for k in range(n + 1, len(lines)):
+                x = lines[k]
+                if not word.search(x):
+                    continue
+                if re.match(r"\S+ %s\b" % reg, x) and not x.startswith(("ds_write", "global_store", "buffer_store")):
+                    break          # the register gets a new value: the draw's life ends here
+                readers.append((k, x))
+            assert readers, (m.group(1), "the draw is never read")
+            for k, x in readers:
+                assert re.match(r"ds_write_b32 v\d+, %s$" % reg, x), (m.group(1), x)
+                back = lines[max(0, k - 40):k]
+                labels = [i for i, y in enumerate(back) if y.startswith(".LBB")]
+                straight = back[labels[-1] + 1:] if labels else back
+                # the wait may sit in the block in front of the predicated store: look through one label
+                window = straight if any("vmcnt(0)" in y for y in straight) else back
+                assert any(y.startswith("s_waitcnt") and "vmcnt(0)" in y for y in window), (m.group(1), x)
+    assert found >= 2   # the two weight-gradient kernels draw their tiles
 
 
 def test_kernels_do_not_spill(ffn_asm):
