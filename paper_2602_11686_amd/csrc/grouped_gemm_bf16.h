@@ -370,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     auto issue_part = [&](int stage, int buf, int lo, int hi) {
         const int sg = stage >= di.nk ? 1 : 0;
         const int k0 = di.kbeg + (stage - sg * di.nk) * TK;
-        const uint32_t st = lds_wave + buf * kStageBytes;
+        const uint32_t st = __builtin_amdgcn_readfirstlane(lds_wave + buf * kStageBytes);
         if constexpr (!RAGK) {
             const char* Ab = (sg ? sA[1] : sA[0]) + (int64_t)k0 * 2;
             const char* Bb = (sg ? sB[1] : sB[0]) + (BT == 1 ? (int64_t)k0 * 2 : (int64_t)k0 * ldb * 2);
