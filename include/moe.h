@@ -36,6 +36,12 @@
  *     moe_last_error().  Data-dependent faults (non-finite values, expert ids
  *     out of range, offsets that do not describe R rows) are undefined
  *     behaviour and are not checked on the device.
+ *   - Device: the grouped-GEMM calls (moe_grouped_ffn_fwd, _fwd_groups, _bwd and, for bf16,
+ *     moe_gate_topk_bwd) are laid out for a whole MI355X (gfx950, 256 compute units: one persistent
+ *     workgroup per unit, dealt round-robin to the 8 XCDs).  They look the current device up once and
+ *     return MOE_ERR_UNSUPPORTED on any other architecture or under a compute-unit mask, and
+ *     MOE_ERR_DEVICE if no device can be queried; nothing is launched in either case.  One-time kernel
+ *     attributes are set under a lock, once per kernel and device: calls may come from several threads.
  *   - Same inputs give bit-identical outputs from run to run (no floating
  *     point atomics; integer atomics only where the order cannot matter).
  */
@@ -173,6 +179,21 @@ moe_status moe_grouped_ffn_fwd_groups(const moe_shape* shape, int32_t G, const i
                                       const void* x_perm, const int32_t* group_offsets, const void* w1,
                                       const void* w3, const void* w2, void* y_perm, void* a_save,
                                       void* b_save, void* ws, size_t ws_bytes, void* stream);
+
+/* moe_grouped_ffn_bwd over replica groups (appendix, lite routing; section 3.1, executor: a device
+ * computes on the replica slots it hosts and the reshard step sums the slots' gradients per expert).
+ * The rows [group_offsets[g], group_offsets[g+1]) are differentiated against the weights of expert
+ * expert_of_group[g] (DEVICE array [G], entries clamped into [0, E-1]); dx_perm is per row as in
+ * moe_grouped_ffn_bwd.  The weight gradients are written PER GROUP:
+ *   dw1_groups, dw3_groups [G, d, f] el,  dw2_groups [G, f, d] el   (a group without rows gets zeros);
+ * the gradient of an expert is the sum over its groups, which is what moe_fsep_reshard forms from the
+ * slots of all devices.  G <= MOE_MAX_EXPERTS.  Everything else as moe_grouped_ffn_bwd. */
+moe_status moe_grouped_ffn_bwd_groups(const moe_shape* shape, int32_t G, const int32_t* expert_of_group,
+                                      const void* x_perm, const int32_t* group_offsets, const void* w1,
+                                      const void* w3, const void* w2, const void* a_save,
+                                      const void* b_save, const void* dy_perm, void* dx_perm /*[R,d]*/,
+                                      void* dw1_groups, void* dw3_groups, void* dw2_groups, void* ws,
+                                      size_t ws_bytes, void* stream);
 
 /* Expert computation, backward (section 3.2 prices it at twice the forward).
  *   dH = dy_perm * w2[e]^T,  dA = dH (.) B (.) silu'(A),  dB = dH (.) silu(A)

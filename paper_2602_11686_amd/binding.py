@@ -25,7 +25,7 @@ EXPORTS = [
     "moe_status_string", "moe_last_error", "moe_abi_version", "moe_workspace_bytes", "moe_gate_topk",
     "moe_permute", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_combine_bwd",
     "moe_gate_topk_bwd", "moe_permute_lite", "moe_grouped_ffn_fwd_groups", "moe_permute_static",
-    "moe_permute_static_max_hist_entries",
+    "moe_permute_static_max_hist_entries", "moe_grouped_ffn_bwd_groups",
 ]
 _NOT_A_STATUS = {"moe_status_string", "moe_last_error", "moe_abi_version", "moe_workspace_bytes",
                  "moe_permute_static_max_hist_entries"}
@@ -230,6 +230,27 @@ def moe_grouped_ffn_bwd(s: Shape, x_perm, offsets, w1, w3, w2, a_save, b_save, d
                                      _ptr(dw3, s.dtype, (s.E, s.d, s.f), "dw3"),
                                      _ptr(dw2, s.dtype, (s.E, s.f, s.d), "dw2"), wp, wn, _stream()),
            "moe_grouped_ffn_bwd")
+
+
+def moe_grouped_ffn_bwd_groups(s: Shape, G: int, expert_of_group, x_perm, group_offsets, w1, w3, w2, a_save, b_save,
+                               dy_perm, dx_perm, dw1_groups, dw3_groups, dw2_groups, ws):
+    c = s.c()
+    wp, wn = _ws(ws)
+    _check(lib().moe_grouped_ffn_bwd_groups(ctypes.byref(c), ctypes.c_int32(G),
+                                            _ptr(expert_of_group, torch.int32, (G,), "expert_of_group"),
+                                            _ptr(x_perm, s.dtype, (s.R, s.d), "x_perm"),
+                                            _ptr(group_offsets, torch.int32, (G + 1,), "group_offsets"),
+                                            _ptr(w1, s.dtype, (s.E, s.d, s.f), "w1"),
+                                            _ptr(w3, s.dtype, (s.E, s.d, s.f), "w3"),
+                                            _ptr(w2, s.dtype, (s.E, s.f, s.d), "w2"),
+                                            _ptr(a_save, s.dtype, (s.R, s.f), "a_save"),
+                                            _ptr(b_save, s.dtype, (s.R, s.f), "b_save"),
+                                            _ptr(dy_perm, s.dtype, (s.R, s.d), "dy_perm"),
+                                            _ptr(dx_perm, s.dtype, (s.R, s.d), "dx_perm"),
+                                            _ptr(dw1_groups, s.dtype, (G, s.d, s.f), "dw1_groups"),
+                                            _ptr(dw3_groups, s.dtype, (G, s.d, s.f), "dw3_groups"),
+                                            _ptr(dw2_groups, s.dtype, (G, s.f, s.d), "dw2_groups"), wp, wn, _stream()),
+           "moe_grouped_ffn_bwd_groups")
 
 
 def moe_unpermute_combine(s: Shape, y_perm, row_of_pair, topk_w, y):

@@ -4,6 +4,9 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
+#include <utility>
+#include <vector>
 
 #include "moe_internal.h"
 
@@ -66,6 +69,53 @@ moe_status check_shape(const moe_shape* s, const char* who) {
         return MOE_ERR_UNSUPPORTED;
     }
     return MOE_OK;
+}
+
+static std::mutex g_dev_mutex;
+static int g_dev_state[64];  // per device: 0 unknown, 1 supported, 2 unsupported
+static char g_dev_why[64][96];
+
+moe_status check_device(const char* who) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        set_error("%s: no usable GPU (hipGetDevice: %s)", who, hipGetErrorString(e));
+        return MOE_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (g_dev_state[dev] == 0) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, dev);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("%s: hipGetDeviceProperties failed: %s", who, hipGetErrorString(e));
+            return MOE_ERR_DEVICE;
+        }
+        const bool arch = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+        const bool cus = prop.multiProcessorCount == 256;
+        g_dev_state[dev] = arch && cus ? 1 : 2;
+        snprintf(g_dev_why[dev], sizeof(g_dev_why[dev]), "%.40s with %d compute units", prop.gcnArchName,
+                 prop.multiProcessorCount);
+    }
+    if (g_dev_state[dev] == 2) {
+        set_error("%s: device %d is %s; the grouped GEMM needs gfx950 with all 256 compute units", who, dev,
+                  g_dev_why[dev]);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    return MOE_OK;
+}
+
+void ensure_dynamic_lds(const void* kernel, int bytes) {
+    static std::mutex m;
+    static std::vector<std::pair<const void*, int>> done;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::lock_guard<std::mutex> lock(m);
+    for (const auto& d : done)
+        if (d.first == kernel && d.second == dev) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    done.emplace_back(kernel, dev);
 }
 
 moe_status launch_status(const char* who) {

@@ -367,12 +367,7 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
                             (RAGK ? (g.M >= 8) : (g.K % TK == 0));
             if (ok) {
                 auto kern = gg256_kernel<AT, BT, DUAL, EPI, RAGK>;
-                static bool attr_done = false;  // per instantiation
-                if (!attr_done) {
-                    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-                    attr_done = true;
-                }
+                ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kGemmLds);
                 (void)R;
                 kern<<<dim3(256), kThreads, kGemmLds, st>>>(g);  // persistent: one workgroup per CU
                 return;
@@ -405,12 +400,7 @@ void launch_gate_dwg_gemm(const void* x, const void* dl_hi, const void* dl_lo, c
     g.lda = d; g.ldb = n_pad; g.strideC = (int64_t)d * n_pad;
     g.C0 = partial; g.ldc = n_pad;
     auto kern = gg256_kernel<1, 0, false, EPI_STORE_F32, true>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  kGemmLds);
-        attr_done = true;
-    }
+    ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kGemmLds);
     kern<<<dim3(256), kThreads, kGemmLds, st>>>(g);
 }
 
@@ -423,12 +413,7 @@ void launch_gate_dx_gemm(const void* dl_hi, const void* dl_lo, const void* wg_pa
     g.lda = n_pad; g.ldb = n_pad; g.strideB = 0;
     g.C0 = dx; g.ldc = d;
     auto kern = gg256_kernel<0, 1, false, EPI_ADD, false>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  kGemmLds);
-        attr_done = true;
-    }
+    ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kGemmLds);
     kern<<<dim3(256), kThreads, kGemmLds, st>>>(g);
 }
 
@@ -483,6 +468,7 @@ static moe_status ffn_fwd_impl(const char* who, const moe_shape* s, int groups, 
         set_error("%s: a_save and b_save must both be given or both be NULL", who);
         return MOE_ERR_INVALID_ARG;
     }
+    MOE_RETURN_IF(check_device(who));
     if (ws_bytes < ffn_fwd_workspace_bytes(s)) {
         set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, ffn_fwd_workspace_bytes(s));
         return MOE_ERR_WORKSPACE_TOO_SMALL;
@@ -522,11 +508,12 @@ extern "C" moe_status moe_grouped_ffn_fwd_groups(const moe_shape* s, int32_t G, 
                         ws_bytes, stream);
 }
 
-extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm, const int32_t* offsets,
-                                          const void* w1, const void* w3, const void* w2, const void* a_save,
-                                          const void* b_save, const void* dy_perm, void* dx_perm, void* dw1, void* dw3,
-                                          void* dw2, void* ws, size_t ws_bytes, void* stream) {
-    const char* who = "moe_grouped_ffn_bwd";
+// groups / expert_of_group as in ffn_fwd_impl; the weight gradients are written per group
+static moe_status ffn_bwd_impl(const char* who, const moe_shape* s, int groups, const int32_t* expert_of_group,
+                               const void* x_perm, const int32_t* offsets, const void* w1, const void* w3,
+                               const void* w2, const void* a_save, const void* b_save, const void* dy_perm,
+                               void* dx_perm, void* dw1, void* dw3, void* dw2, void* ws, size_t ws_bytes,
+                               void* stream) {
     MOE_RETURN_IF(check_shape(s, who));
     MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who));
     MOE_RETURN_IF(check_ptr(offsets, "offsets", who));
@@ -541,6 +528,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     MOE_RETURN_IF(check_ptr(dw3, "dw3", who));
     MOE_RETURN_IF(check_ptr(dw2, "dw2", who));
     MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    MOE_RETURN_IF(check_device(who));
     if (ws_bytes < ffn_bwd_workspace_bytes(s)) {
         set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, ffn_bwd_workspace_bytes(s));
         return MOE_ERR_WORKSPACE_TOO_SMALL;
@@ -555,18 +543,19 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     int32_t* order = static_cast<int32_t*>(cv.take(1024));
     void* zero_row = cv.take(512);
     uint32_t* sched = static_cast<uint32_t*>(cv.take(kBwdLaunches * kSchedBytes));
-    expert_order_kernel<<<1, 256, 0, st>>>(offsets, s->E, order, static_cast<uint32_t*>(zero_row), sched,
+    expert_order_kernel<<<1, 256, 0, st>>>(offsets, groups, order, static_cast<uint32_t*>(zero_row), sched,
                                            kBwdLaunches * kSchedWords);
     if (!a_save || !b_save) {  // expert-only recomputation: rebuild A and B (H is rewritten below anyway)
         void* A = cv.take(rf);
         void* B = cv.take(rf);
-        run_fwd1(s, x_perm, offsets, w1, w3, H, A, B, st);
+        run_fwd1(s, x_perm, offsets, w1, w3, H, A, B, st, groups, expert_of_group);
         a_save = A;
         b_save = B;
     }
     {  // dH = dYp * W2^T, then the SwiGLU derivative in the epilogue
         GArgs g{};
-        g.offsets = offsets; g.E = s->E; g.N = s->f; g.K = s->d; g.nseg = 1;
+        g.offsets = offsets; g.E = groups; g.N = s->f; g.K = s->d; g.nseg = 1;
+        g.expert_of_group = expert_of_group; g.n_weights = s->E;
         g.seg[0] = {dy_perm, w2, nullptr};
         g.lda = s->d; g.ldb = s->d; g.strideB = (int64_t)s->f * s->d;
         g.C0 = H; g.C1 = dA; g.C2 = dB; g.S0 = a_save; g.S1 = b_save; g.ldc = s->f;
@@ -574,7 +563,8 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     }
     {  // dXp = dA * W1^T + dB * W3^T
         GArgs g{};
-        g.offsets = offsets; g.E = s->E; g.N = s->d; g.K = s->f; g.nseg = 2;
+        g.offsets = offsets; g.E = groups; g.N = s->d; g.K = s->f; g.nseg = 2;
+        g.expert_of_group = expert_of_group; g.n_weights = s->E;
         g.seg[0] = {dA, w1, nullptr};
         g.seg[1] = {dB, w3, nullptr};
         g.lda = s->f; g.ldb = s->f; g.strideB = (int64_t)s->d * s->f;
@@ -583,7 +573,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     }
     {  // dW2[e] = H_e^T * dYp_e
         GArgs g{};
-        g.offsets = offsets; g.E = s->E; g.M = s->f; g.N = s->d; g.nseg = 1;
+        g.offsets = offsets; g.E = groups; g.M = s->f; g.N = s->d; g.nseg = 1;
         g.seg[0] = {H, dy_perm, nullptr};
         g.lda = s->f; g.ldb = s->d; g.strideC = (int64_t)s->f * s->d;
         g.C0 = dw2; g.ldc = s->d; g.order = order; g.zero_row = zero_row;
@@ -592,7 +582,7 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
     }
     {  // [dW1|dW3][e] = Xp_e^T * [dA_e|dB_e]
         GArgs g{};
-        g.offsets = offsets; g.E = s->E; g.M = s->d; g.N = s->f; g.nseg = 1;
+        g.offsets = offsets; g.E = groups; g.M = s->d; g.N = s->f; g.nseg = 1;
         g.seg[0] = {x_perm, dA, dB};
         g.lda = s->d; g.ldb = s->f; g.strideC = (int64_t)s->d * s->f;
         g.C0 = dw1; g.C1 = dw3; g.ldc = s->f; g.order = order; g.zero_row = zero_row;
@@ -600,4 +590,29 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
         launch_gg<1, 0, true, EPI_STORE2, true>(s, g, R, st);
     }
     return launch_status(who);
+}
+
+
+extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm, const int32_t* offsets,
+                                          const void* w1, const void* w3, const void* w2, const void* a_save,
+                                          const void* b_save, const void* dy_perm, void* dx_perm, void* dw1, void* dw3,
+                                          void* dw2, void* ws, size_t ws_bytes, void* stream) {
+    return ffn_bwd_impl("moe_grouped_ffn_bwd", s, s ? s->E : 0, nullptr, x_perm, offsets, w1, w3, w2, a_save, b_save,
+                        dy_perm, dx_perm, dw1, dw3, dw2, ws, ws_bytes, stream);
+}
+
+extern "C" moe_status moe_grouped_ffn_bwd_groups(const moe_shape* s, int32_t G, const int32_t* expert_of_group,
+                                                 const void* x_perm, const int32_t* group_offsets, const void* w1,
+                                                 const void* w3, const void* w2, const void* a_save,
+                                                 const void* b_save, const void* dy_perm, void* dx_perm,
+                                                 void* dw1_groups, void* dw3_groups, void* dw2_groups, void* ws,
+                                                 size_t ws_bytes, void* stream) {
+    const char* who = "moe_grouped_ffn_bwd_groups";
+    if (G < 1 || G > MOE_MAX_EXPERTS) {
+        set_error("%s: G=%d must be in [1, %d]", who, G, MOE_MAX_EXPERTS);
+        return MOE_ERR_INVALID_ARG;
+    }
+    MOE_RETURN_IF(check_ptr(expert_of_group, "expert_of_group", who));
+    return ffn_bwd_impl(who, s, G, expert_of_group, x_perm, group_offsets, w1, w3, w2, a_save, b_save, dy_perm, dx_perm,
+                        dw1_groups, dw3_groups, dw2_groups, ws, ws_bytes, stream);
 }

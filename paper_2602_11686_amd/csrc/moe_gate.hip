@@ -572,12 +572,7 @@ extern "C" moe_status moe_gate_topk(const moe_shape* s, const void* x, const voi
         if (lds < (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float)) lds = (size_t)kGateMT * MOE_MAX_EXPERTS * sizeof(float);
 #define MOE_GATE_LAUNCH(N, W)                                                                                      \
     {                                                                                                              \
-        static bool attr = false;                                                                                  \
-        if (!attr) {                                                                                               \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_topk_mfma_kernel<N, W>),                 \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kGateMT * 256 * 4);          \
-            attr = true;                                                                                           \
-        }                                                                                                          \
+        ensure_dynamic_lds(reinterpret_cast<const void*>(&gate_topk_mfma_kernel<N, W>), 4 * kGateMT * 256 * 4);    \
         gate_topk_mfma_kernel<N, W><<<grid, W * 64, lds, st>>>(static_cast<const bf16_t*>(x), wgT, bias, topk_ids, \
                                                                topk_w, logits_out, s->T, s->d, s->E, s->k);        \
     }
@@ -643,12 +638,7 @@ static moe_status gate_bwd_launch(const moe_shape* s, const T* x, const T* w_gat
         launch_gate_bwd_dx<T>(dx, wgT, ids, dl, s->T, s->d, s->k, st);
     }
     const size_t lds = (size_t)s->E * kDwgSlab * sizeof(float);
-    static thread_local bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_bwd_dwg_partial_kernel<T>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, MOE_MAX_EXPERTS * kDwgSlab * 4);
-        attr_set = true;
-    }
+    ensure_dynamic_lds(reinterpret_cast<const void*>(&gate_bwd_dwg_partial_kernel<T>), MOE_MAX_EXPERTS * kDwgSlab * 4);
     dim3 grid((s->d + kDwgSlab - 1) / kDwgSlab, nchunks);
     gate_bwd_dwg_partial_kernel<T><<<grid, kDwgSlab, lds, st>>>(x, ids, dl, partial, s->T, s->d, s->E, s->k);
     gate_bwd_dwg_reduce_kernel<<<256, 256, 0, st>>>(partial, dwg, nchunks, s->d, s->E);
@@ -668,6 +658,7 @@ extern "C" moe_status moe_gate_topk_bwd(const moe_shape* s, const void* x, const
     MOE_RETURN_IF(check_ptr(dx_inout, "dx_inout", who, true));
     MOE_RETURN_IF(check_ptr(dw_gate, "dw_gate", who));
     MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    if (s->dtype == MOE_BF16 && s->d % 8 == 0) MOE_RETURN_IF(check_device(who));  // (this path runs the grouped GEMM)
     if (ws_bytes < gate_bwd_workspace_bytes(s)) {
         set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, gate_bwd_workspace_bytes(s));
         return MOE_ERR_WORKSPACE_TOO_SMALL;

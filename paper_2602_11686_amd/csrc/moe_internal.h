@@ -15,6 +15,13 @@ moe_status check_shape(const moe_shape* s, const char* who);
 bool aligned16(const void* p);
 moe_status check_ptr(const void* p, const char* name, const char* who, bool nullable = false);
 moe_status launch_status(const char* who);
+// The persistent grouped GEMM is laid out for a whole MI355X: 256 workgroups, one per compute unit, dealt
+// round-robin to 8 XCDs.  MOE_OK on such a device (the answer is looked up once per device and kept),
+// MOE_ERR_DEVICE if no device can be queried, MOE_ERR_UNSUPPORTED on anything else (another architecture, a
+// compute-unit mask).
+moe_status check_device(const char* who);
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per (kernel, device); safe to call from any thread.
+void ensure_dynamic_lds(const void* kernel, int bytes);
 
 inline size_t el_size(const moe_shape* s) { return s->dtype == MOE_BF16 ? 2 : 4; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

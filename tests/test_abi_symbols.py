@@ -63,3 +63,35 @@ def test_host_side_validation_needs_no_gpu():
                        ctypes.c_void_p(16), ctypes.c_void_p(16), ctypes.c_void_p(16), ctypes.c_void_p(16), ctypes.c_size_t(1), None)
     assert st == 3
     assert L.moe_status_string(3) == b"workspace too small"
+
+
+def test_grouped_gemm_calls_refuse_to_run_without_a_supported_device():
+    """Where no GPU can be queried the grouped-GEMM entry points return MOE_ERR_DEVICE before launching anything
+    (on a GPU machine this test is skipped: the fake pointers below must never reach a kernel)."""
+    from paper_2602_11686_amd import binding as B
+    import torch
+    if not os.path.exists(B.LIB_PATH):
+        pytest.skip("libmoe.so not built")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present: the device check passes and the call would launch")
+    L = B.lib()
+    c = B.Shape(64, 128, 256, 4, 2, torch.bfloat16).c()
+    p = ctypes.c_void_p(4096)
+    big = ctypes.c_size_t(1 << 40)
+    st = L.moe_grouped_ffn_fwd(ctypes.byref(c), p, p, p, p, p, p, None, None, p, big, None)
+    assert st == 4 and b"GPU" in L.moe_last_error()
+    st = L.moe_grouped_ffn_bwd(ctypes.byref(c), p, p, p, p, p, None, None, p, p, p, p, p, p, big, None)
+    assert st == 4
+    st = L.moe_gate_topk_bwd(ctypes.byref(c), p, p, p, p, p, p, p, p, big, None)
+    assert st == 4
+    # argument errors still come first
+    st = L.moe_grouped_ffn_fwd(ctypes.byref(c), None, p, p, p, p, p, None, None, p, big, None)
+    assert st == 1
+
+
+def test_one_time_kernel_attributes_are_set_under_a_lock():
+    """The launch helpers hold no unsynchronised `static bool` flags any more."""
+    csrc = os.path.join(ROOT, "paper_2602_11686_amd", "csrc")
+    for name in os.listdir(csrc):
+        text = open(os.path.join(csrc, name)).read()
+        assert not re.search(r"static\s+(thread_local\s+)?bool\s+attr", text), name

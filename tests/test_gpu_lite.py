@@ -170,3 +170,68 @@ def test_layer_over_replica_groups(T, d, f, E, k, N, C, Dn, rank):
     Y = O.unpermute_combine(Yp, rop_ref, wts.astype(np.float64), T)
     assert rel_max(host(yp_l), Yp) <= TOL[torch.bfloat16]
     assert rel_max(host(y_l), Y) <= TOL[torch.bfloat16]
+
+
+@pytest.mark.parametrize("T,d,f,E,k,N,C,Dn,rank", [(600, 256, 192, 8, 2, 8, 2, 4, 3), (900, 128, 256, 16, 4, 8, 4, 4, 0)])
+def test_backward_over_replica_groups(T, d, f, E, k, N, C, Dn, rank):
+    """moe_grouped_ffn_bwd_groups: dx_perm per row against the oracle's FFN backward over the groups (weights
+    gathered per group), and the per-group weight gradients summed over the groups of an expert against the
+    oracle's per-expert gradients of the plain layout (the reshard step sums replica gradients).  Every
+    expert's block is compared on its own scale; saved and recomputed activations give the same bits."""
+    print(f"case T={T} d={d} f={f} E={E} k={k}", flush=True)
+    rng = np.random.default_rng(T + 1)
+    bits = lambda a: I.f32_to_bf16_bits(a.astype(np.float32))
+    xb = bits(rng.standard_normal((T, d))); w1b = bits(rng.standard_normal((E, d, f)) * 0.05)
+    w3b = bits(rng.standard_normal((E, d, f)) * 0.05); w2b = bits(rng.standard_normal((E, f, d)) * 0.05)
+    ids = random_ids(T, T, E, k)
+    G, eog, dog, rb, rg = layout_for(ids, E, N, C, Dn, rank, seed=2)
+    to = lambda b: torch.tensor(b.view(np.int16), device="cuda").view(torch.bfloat16)
+    x, w1, w3, w2 = to(xb), to(w1b), to(w3b), to(w2b)
+    s = B.Shape(T, d, f, E, k, torch.bfloat16)
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    ec, gc, go, rop_l, por_l, xp_l, err = run_permute_lite(s, G, x, ids, rb, rg)
+    assert int(err[0]) == 0
+    dypb = bits(rng.standard_normal((s.R, d)))
+    dyp = to(dypb)
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    yp = torch.empty(s.R, d, **bf); a = torch.empty(s.R, f, **bf); b = torch.empty(s.R, f, **bf)
+    eog_d = i32(eog)
+    B.moe_grouped_ffn_fwd_groups(s, G, eog_d, xp_l, go, w1, w3, w2, yp, a, b, ws)
+    outs = []
+    for saved in (True, False):
+        dxp = torch.full((s.R, d), float("nan"), **bf)
+        dw1 = torch.full((G, d, f), float("nan"), **bf); dw3 = torch.full((G, d, f), float("nan"), **bf)
+        dw2 = torch.full((G, f, d), float("nan"), **bf)
+        B.moe_grouped_ffn_bwd_groups(s, G, eog_d, xp_l, go, w1, w3, w2, a if saved else None, b if saved else None,
+                                     dyp, dxp, dw1, dw3, dw2, ws)
+        torch.cuda.synchronize()
+        outs.append((dxp, dw1, dw3, dw2))
+    for p, q in zip(*outs):
+        assert torch.equal(p.view(torch.int16), q.view(torch.int16))
+    dxp, dw1, dw3, dw2 = outs[0]
+    # oracle over the groups: FFN backward with the weights gathered per group
+    f64 = lambda v: I.bf16_bits_to_f32(v).astype(np.float64)
+    go_ref = host(go).astype(np.int32)
+    e = np.asarray(eog)
+    Xp = f64(xb)[host(por_l) // k]
+    ref_dxp, g1, g3, g2 = O.ffn_bwd(Xp, go_ref, f64(w1b)[e], f64(w3b)[e], f64(w2b)[e], f64(dypb))
+    tol = TOL[torch.bfloat16]
+    groups = [slice(int(go_ref[g]), int(go_ref[g + 1])) for g in range(G)]
+    from tests.helpers import rel_max_blocks
+    assert rel_max(host(dxp), ref_dxp) <= tol
+    err_b, gi = rel_max_blocks(host(dxp), ref_dxp, groups)
+    assert err_b <= tol, ("dXp", "group", gi, err_b)
+    for name, got, want in (("dW1", dw1, g1), ("dW3", dw3, g3), ("dW2", dw2, g2)):
+        got = host(got)
+        assert np.isfinite(got).all(), name
+        err_b, gi = rel_max_blocks(got, want, range(G))
+        assert err_b <= tol, (name, "group", gi, err_b)
+        # summed over the groups of an expert: the expert's gradient in the plain (un-replicated) layout
+        summed = np.zeros((E,) + got.shape[1:])
+        np.add.at(summed, e, got)
+        want_e = np.zeros_like(summed)
+        np.add.at(want_e, e, want)
+        err_e, ei = rel_max_blocks(summed, want_e, range(E))
+        assert err_e <= tol, (name, "expert", ei, err_e)
+    for g in np.nonzero(np.diff(go_ref) == 0)[0]:
+        assert float(dw1[g].abs().max()) == 0 and float(dw2[g].abs().max()) == 0 and float(dw3[g].abs().max()) == 0
