@@ -341,6 +341,22 @@ def ceilings_leg():
         torch.cuda.synchronize()
         out[name] = round(fl * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
     out["dense_gemm_shape"] = {"rows": T, "d": d, "f": f, "experts": 1}
+    # The vendor library's plain bf16 GEMM (torch.matmul, no epilogue) in this run, as context for the dense
+    # figures above: the forward's operand layout (B row-major [K, N]) and the backward's (B as [N, K]).
+    del xp, dyp, w1, w3, w2, yp, dxp, a, b, dw1, dw3, dw2
+    M, K, N = 8192, 4096, 8192
+    am, bn, bt = rn(M, K), rn(K, N), rn(N, K)
+    for name, fn in (("library_gemm_nn_tflops", lambda: am @ bn), ("library_gemm_nt_tflops", lambda: am @ bt.t())):
+        for _ in range(3):
+            fn()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(20):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(2.0 * M * K * N * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    out["library_gemm_shape"] = {"M": M, "K": K, "N": N}
     return out
 
 
@@ -439,10 +455,12 @@ def main():
                 shared.clear()
                 oinp = shared[key] = I.layer_inputs(ow)
             oinp = dict(oinp, bias=I.gate_bias(ow))
-            o = run_workload(ow, steps=20, warmup=5, inp=oinp)
+            # short layers get more steps, so that every timed region is some 0.2 s long (the clocks settle)
+            o_steps = 200 if ow.d * ow.f * ow.T * ow.k < 2 ** 40 else (60 if not ow.backward or ow.d * ow.f < 2 ** 24 else 20)
+            o = run_workload(ow, steps=o_steps, warmup=10, inp=oinp)
             others[name] = {"ms_per_step": round(o["ms_per_step"], 4), "tokens_per_s": round(o["tokens_per_s"], 1),
                             "pass": o["config"]["pass"], "max_over_mean_load": o["config"]["max_over_mean_load"],
-                            "empty_experts": o["config"]["empty_experts"], "steps": 20, "warmup": 5,
+                            "empty_experts": o["config"]["empty_experts"], "steps": o_steps, "warmup": 10,
                             "ffn_tflops": round(o["achieved"], 1), "frac": round(o["achieved"] / PEAK_BF16_TFLOPS, 4),
                             "hbm": {n: {"gbs": v["achieved"], "frac": v["frac"]} for n, v in o["hbm"].items()}}
             torch.cuda.empty_cache()

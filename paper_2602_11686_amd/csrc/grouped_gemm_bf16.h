@@ -46,7 +46,19 @@ constexpr int kWN = kWaves / 2;            // wavefronts along N (two along M)
 constexpr int NJ = 8 / kWN;                // 32-column MFMA blocks per wavefront
 constexpr int CPW = 32 / kWaves;           // 1 KB DMA chunks per wavefront per operand tile
 constexpr int kSteps = TK / 16;            // MFMA k-steps per stage
-constexpr int kGemmLds = kStages * kStageBytes + 2 * (MOE_MAX_EXPERTS + 1) * 4 + 16;  // stages + expert table + 2 draw slots
+// LDS map (160 KB): the two stage buffers, then the epilogue's staging area, then the expert table and the
+// two draw slots.  The staging area (32 KB) does not fit behind the stage buffers: it starts inside the last
+// kDeferChunks 1 KB chunks of the second buffer's B half.  Those chunks (the last ones wavefront 7 loads)
+// are requested after the epilogue when a tile's first two stages are requested in front of it.
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int kTableBytes = 2 * (MOE_MAX_EXPERTS + 1) * 4 + 16;            // expert table + 2 draw slots
+constexpr int kTableOff = (kLdsBytes - kTableBytes) & ~15;
+constexpr int kStagingBytes = 32768;
+constexpr int kStagingOff = kTableOff - kStagingBytes;
+constexpr int kDeferChunks = (kStages * kStageBytes - kStagingOff + 1023) / 1024;
+static_assert(kStagingOff >= kStages * kStageBytes - CPW * 1024 + 1024 && kDeferChunks >= 1 && kDeferChunks < CPW,
+              "the staging area may only reach into chunks that one wavefront loads last");
+constexpr int kGemmLds = kLdsBytes;
 // Tile queues (GArgs::sched): one counter per XCD, kSchedStride words apart, all zero when the kernel starts.
 constexpr int kSchedStride = 32;
 constexpr int kSchedWords = 8 * kSchedStride;
@@ -149,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     static_assert(RAGK ? (AT == 1 && BT == 0) : (AT == 0), "operand forms");
     static_assert(!(DUAL && BT == 1), "two B matrices are taken in k-row form only");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    int32_t* t_off = reinterpret_cast<int32_t*>(smem + kStages * kStageBytes);  // [E+1] rows of each expert
+    int32_t* t_off = reinterpret_cast<int32_t*>(smem + kTableOff);  // [E+1] rows of each expert
     int32_t* t_pref = t_off + MOE_MAX_EXPERTS + 1;                              // [E+1] tiles before expert e
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / kWN, wn = wave % kWN;  // 2 x kWN wavefronts, 128 rows x 32*NJ columns each
@@ -485,6 +497,10 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             }
         }
     };
+    // The MFMAs take the B fragment as their first operand and the A fragment as their second: each 32x32
+    // block is accumulated transposed, so that a lane holds runs of four consecutive COLUMNS of one row
+    // (row = lane%32, column = 8*(r/4) + 4*(lane/32) + r%4) and the epilogues write whole 8- or 16-byte
+    // pieces of output rows without exchanging values between lanes.
     f32x16 acc[4][NJ];
     auto zero_acc = [&]() {
 #pragma unroll
@@ -500,7 +516,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     };
     // The accumulators as operands of an empty volatile asm: every MFMA issued so far stays in front of
     // the waits and the barrier that follow (instruction selection otherwise moves most of a k-step's
@@ -516,10 +532,10 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             for (int j = 0; j < NJ; ++j) pin_one(acc[i][j]);
     };
 
-    // ---- epilogue of one tile.  The accumulators (col = lane%32, row = 8*(r/4) + 4*(lane/32) + r%4
-    // inside a 32x32 block) go through LDS, 64 rows at a time (block i of both wavefront rows), so that
-    // global memory sees 16-byte accesses along rows.  `stg` is the second stage buffer (64 KB: two staging
-    // areas of 32 KB); the first one already receives the next tile's first stage.
+    // ---- epilogue of one tile.  The accumulators (row = lane%32, col = 8*(r/4) + 4*(lane/32) + r%4
+    // inside a 32x32 block) go through LDS, 16 KB (bf16) or 32 KB (fp32) at a time, so that global memory
+    // sees 16-byte accesses along rows.  `stg` is the staging area; both stage buffers already receive the
+    // next tile's first two stages (but for the chunks the staging area overlaps).
     auto epilogue_zero = [&](const TileDesc& t) {  // ragged K, expert without rows: exact zeros, no staging needed
         const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
         {
@@ -541,28 +557,39 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         }
     };
     auto epilogue = [&](const TileDesc& t, char* stg) {
+        // The thread's coordinates, derived afresh from an opaque copy of its index: everything the epilogue
+        // computes from them is then recomputed per tile (a few VALU instructions) instead of living in
+        // registers through the main loop, where the budget is 256 VGPRs.
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63, wave = tid >> 6;
+        const int wm = wave / kWN, wn = wave % kWN, l32 = lane & 31, kg = lane >> 5;
         const int64_t cbase = RAGK ? (int64_t)t.e * g.strideC : 0;
         // a 128-row tile holds two row blocks per wavefront, the rows of wavefront row 1 start at 64
         const bool half = !RAGK && t.half;
         const int ni = half ? 2 : 4, wrows = half ? 64 : 128;
         if constexpr (EPI == EPI_STORE_F32) {  // narrow fp32 output (gate weight gradient): direct stores
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i) {
+                if (i >= ni) continue;
+                const int row = t.m0 + wm * wrows + i * 32 + l32;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    if (i >= ni) continue;
-                    const int row = t.m0 + wm * wrows + i * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) {
-                        const int col = t.n0 + wn * NJ * 32 + j * 32 + l32;
-                        if (row < t.m_lim && col < g.N)
-                            static_cast<float*>(g.C0)[cbase + (int64_t)row * g.ldc + col] = acc[i][j][r];
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const int col = t.n0 + wn * NJ * 32 + j * 32 + g4 * 8 + kg * 4;
+                        if (row >= t.m_lim) continue;
+                        float* d = static_cast<float*>(g.C0) + cbase + (int64_t)row * g.ldc + col;
+#pragma unroll
+                        for (int z = 0; z < 4; ++z)
+                            if (col + z < g.N) d[z] = acc[i][j][4 * g4 + z];
                     }
-                }
+            }
         } else if constexpr (EPI == EPI_DH || EPI == EPI_ADD) {
             // dH in fp32 through LDS, 64 rows x 128 columns at a time; then 8 columns per thread: read A, B,
-            // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).  Staging rows are 512 B; the
-            // 16-byte piece index is XORed with 8*((row>>2)&1) so that the two lane halves hit different banks.
+            // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).  Staging rows are 512 B; a lane writes
+            // 16-byte pieces of its row, and the piece index is XORed with row%32 so that the 32 rows of a
+            // write fall into different banks.
             // The global operands of a pass (saved A and B, or the old C) are requested before the staging
             // writes, so that they travel while the accumulators go through LDS.  Every lane loads (dead items
             // from a clamped address) and every lane consumes what it loaded; only the stores are predicated.
@@ -579,7 +606,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                     bool live[IPT];
 #pragma unroll
                     for (int u = 0; u < IPT; ++u) {
-                        const int item = threadIdx.x + u * kThreads;
+                        const int item = tid + u * kThreads;
                         const int sr = item >> 4, cg = item & 15;
                         const int grow = t.m0 + (sr >> 5) * wrows + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
                         live[u] = grow < t.m_lim && gcol < g.N && i < ni;
@@ -595,16 +622,16 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                         }
                     }
                     {
+                        const int sr = wm * 32 + l32;
 #pragma unroll
                         for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int sr = wm * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
-                                const int tcol = wn * NJ * 32 + j * 32 + l32;  // column inside the 256-wide tile
-                                const int col = tcol & 127;
-                                const int piece = (col >> 2) ^ (((sr >> 2) & 1) << 3);
+                            for (int g4 = 0; g4 < 4; ++g4) {
+                                const int tcol = wn * NJ * 32 + j * 32 + g4 * 8 + kg * 4;  // column inside the 256-wide tile
+                                const int piece = ((tcol & 127) >> 2) ^ (sr & 31);
                                 if ((tcol >> 7) == p)
-                                    *reinterpret_cast<float*>(stg + sr * 512 + piece * 16 + (col & 3) * 4) = acc[i][j][r];
+                                    *reinterpret_cast<f32x4v*>(stg + sr * 512 + piece * 16) =
+                                        (f32x4v){acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]};
                             }
                     }
                     __syncthreads();
@@ -614,10 +641,10 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                     __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
                     for (int u = 0; u < IPT; ++u) {
-                        const int item = threadIdx.x + u * kThreads;
+                        const int item = tid + u * kThreads;
                         const int sr = item >> 4, cg = item & 15;
                         const int64_t idx = idxs[u];
-                        const int sw = ((sr >> 2) & 1) << 3;
+                        const int sw = sr & 31;
                         const f32x4v d0 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg) ^ sw) * 16);
                         const f32x4v d1 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg + 1) ^ sw) * 16);
                         const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
@@ -663,55 +690,59 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                 }
             }
         } else {
-            // bf16 tiles: stage [64 rows][ROWB bytes] with swizzled 16-byte pieces, then 16 bytes per lane along rows.
-            // Two staging areas (the halves of the second stage buffer) take the
-            // passes in turn, so one barrier per pass is enough: a wavefront that writes pass p+2 has passed the
-            // barrier of pass p+1, which every wavefront reaches only after it has read pass p.
+            // bf16 tiles: stage [RPP rows][ROWB bytes] with swizzled 16-byte pieces, then 16 bytes per lane along
+            // rows.  A pass fills one of two 16 KB areas: block i of both wavefront rows (64 rows of 256 B) or of
+            // one wavefront row (32 rows of 512 B).  The areas take the passes in turn, so one barrier per pass is
+            // enough: a wavefront that writes pass p+2 has passed the barrier of pass p+1, which every wavefront
+            // reaches only after it has read pass p.
             constexpr int ROWB = (DUAL && EPI == EPI_SWIGLU) ? 256 : 512;
-            constexpr int PPR = ROWB / 16;  // pieces per row
-            // Four accumulators r = 4g .. 4g+3 of a lane are four consecutive rows of one column.  A 4x4
-            // transpose inside each quad of lanes (two packed conversions, then two exchanges of packed pairs over
-            // DPP: with the neighbouring lane, merged by a byte permute, and with the lane two apart) leaves lane q
-            // of the quad with row q, columns c .. c+3: one 8-byte LDS write per four values.
-            // Staging swizzle: piece ^ 4*(row & 3) puts the four rows of a quad's write 64 bytes apart in the banks.
-            const int q4 = lane & 3;
-            const bool odd = (q4 & 1) != 0, upper = (q4 >> 1) != 0;
-            auto stg_sw = [](int sr) { return (sr & 3) << 2; };
-            // byte selector of the first exchange (v_perm_b32 over {own pair, neighbour's pair}): the even lane of
-            // a pair keeps the low halves (row 0 resp. 2: its own column, then the neighbour's), the odd lane the
-            // high halves (row 1 resp. 3: the neighbour's column, then its own)
-            const uint32_t sel1 = odd ? 0x07060302u : 0x01000504u;
+            constexpr int PPR = ROWB / 16;               // pieces per row
+            constexpr int RPP = kStagingBytes / 2 / ROWB;  // rows per pass: 64 or 32
+            constexpr int ITEMS = RPP * PPR / kThreads;   // 16-byte pieces per thread and pass
+            static_assert(ITEMS * kThreads == RPP * PPR, "a pass is a whole number of pieces per thread");
+            // Four accumulators r = 4g .. 4g+3 of a lane are four consecutive columns of its row: one 8-byte
+            // LDS write.  Staging swizzle: piece ^ (row % PPR), so that the rows of one write (32 lanes, 32
+            // rows, the same piece) fall into different banks.
+            auto stg_sw = [](int sr) { return sr & (PPR - 1); };
             auto put4 = [&](char* sb, int g4, int colbase, float v0, float v1, float v2, float v3) {
-                auto swap1 = [](uint32_t x) {
-                    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xf, 0xf, true);  // quad_perm [1,0,3,2]
-                };
-                const uint32_t c01 = pack_bf16x2(v0, v1), c23 = pack_bf16x2(v2, v3);  // this lane's column, rows (0,1), (2,3)
-                const uint32_t p01 = __builtin_amdgcn_perm(c01, swap1(c01), sel1);    // row 0 | 1, columns (even, odd) of the pair
-                const uint32_t p23 = __builtin_amdgcn_perm(c23, swap1(c23), sel1);    // row 2 | 3
-                const uint32_t got = (uint32_t)__builtin_amdgcn_mov_dpp((int)(upper ? p01 : p23), 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
                 u32x2 o;
-                o[0] = upper ? got : p01;  // lanes 0, 1: rows 0, 1 (own pair, then the pair of the lane two up)
-                o[1] = upper ? p23 : got;  // lanes 2, 3: rows 2, 3
-                const int sr = wm * 32 + g4 * 8 + kg * 4 + q4;
-                const int col = colbase + (l32 & ~3);
+                o[0] = pack_bf16x2(v0, v1);
+                o[1] = pack_bf16x2(v2, v3);
+                const int sr = (RPP == 64 ? wm * 32 : 0) + l32;
+                const int col = colbase + g4 * 8 + kg * 4;
                 *reinterpret_cast<u32x2*>(sb + sr * ROWB + (((col >> 3) ^ stg_sw(sr)) << 4) + (col & 7) * 2) = o;
             };
-            auto flush = [&](const char* sb, int i, bf16_t* dst0, bf16_t* dst1, int cols0) {
+            const int64_t tile_base = cbase + (int64_t)t.m0 * g.ldc + t.n0;
+            // (opaque per tile: the store offsets below do not change from tile to tile, and the compiler would
+            // otherwise compute them once per kernel and keep them in scratch memory)
+            uint32_t ldc_u = (uint32_t)g.ldc;
+            asm volatile("" : "+s"(ldc_u));
+            // h: the wavefront row whose 32 rows the pass holds (RPP == 32)
+            auto flush = [&](const char* sb, int i, int h, bf16_t* dst0, bf16_t* dst1, int cols0) {
                 __syncthreads();
-                for (int item = threadIdx.x; item < 64 * PPR; item += kThreads) {
-                    const int sr = item / PPR, pc = item - sr * PPR;
-                    const int grow = t.m0 + (sr >> 5) * wrows + i * 32 + (sr & 31);
+                u32x4 v[ITEMS];
+#pragma unroll
+                for (int u = 0; u < ITEMS; ++u) {
+                    const int item = tid + u * kThreads;
+                    const int sr = item / PPR, pc = item % PPR;
+                    v[u] = *reinterpret_cast<const u32x4*>(sb + sr * ROWB + ((pc ^ stg_sw(sr)) << 4));
+                }
+#pragma unroll
+                for (int u = 0; u < ITEMS; ++u) {
+                    const int item = tid + u * kThreads;
+                    const int sr = item / PPR, pc = item % PPR;
+                    const int trow = (RPP == 64 ? (sr >> 5) : h) * wrows + i * 32 + (sr & 31);  // row inside the tile
                     int col = pc * 8;
                     bf16_t* dst = dst0;
                     if (dst1 && col >= cols0) { col -= cols0; dst = dst1; }
-                    const int gcol = t.n0 + col;
-                    if (grow < t.m_lim && gcol < g.N)
-                        *reinterpret_cast<u32x4*>(dst + cbase + (int64_t)grow * g.ldc + gcol) =
-                            *reinterpret_cast<const u32x4*>(sb + sr * ROWB + ((pc ^ stg_sw(sr)) << 4));
+                    // (offsets inside a tile fit 32 bits: at most 256 rows of ldc < 2^22 elements)
+                    const uint32_t off = (uint32_t)trow * ldc_u + (uint32_t)col;
+                    if (t.m0 + trow < t.m_lim && t.n0 + col < g.N)
+                        *reinterpret_cast<u32x4*>(dst + tile_base + off) = v[u];
                 }
             };
             int pn = 0;  // passes so far
-            auto next_buf = [&]() { return stg + ((pn++ & 1) ? kStageBytes / 2 : 0); };  // the two areas in turn
+            auto next_buf = [&]() { return stg + ((pn++ & 1) ? kStagingBytes / 2 : 0); };  // the two areas in turn
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (i >= ni) break;
@@ -732,39 +763,46 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                             }
                         bf16_t* dst = pass == 0 ? static_cast<bf16_t*>(g.C0)
                                                 : const_cast<bf16_t*>(static_cast<const bf16_t*>(pass == 1 ? g.S0 : g.S1));
-                        flush(sb, i, dst, nullptr, 0);
+                        flush(sb, i, 0, dst, nullptr, 0);
                     }
-                } else if constexpr (DUAL) {  // EPI_STORE2: first 128 columns -> C0, second 128 -> C1
-                    char* sb = next_buf();
+                } else {
 #pragma unroll
-                    for (int j = 0; j < NJ / 2; ++j)
+                    for (int h = 0; h < 2; ++h) {
+                        char* sb = next_buf();
+                        if (wm == h) {
+                            if constexpr (DUAL) {  // EPI_STORE2: first 128 columns -> C0, second 128 -> C1
 #pragma unroll
-                        for (int g4 = 0; g4 < 4; ++g4) {
-                            const int r = 4 * g4;
-                            put4(sb, g4, wn * (NJ / 2) * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1], acc[i][j][r + 2], acc[i][j][r + 3]);
-                            put4(sb, g4, 128 + wn * (NJ / 2) * 32 + j * 32, acc[i][j + NJ / 2][r], acc[i][j + NJ / 2][r + 1],
-                                 acc[i][j + NJ / 2][r + 2], acc[i][j + NJ / 2][r + 3]);
+                                for (int j = 0; j < NJ / 2; ++j)
+#pragma unroll
+                                    for (int g4 = 0; g4 < 4; ++g4) {
+                                        const int r = 4 * g4;
+                                        put4(sb, g4, wn * (NJ / 2) * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1], acc[i][j][r + 2],
+                                             acc[i][j][r + 3]);
+                                        put4(sb, g4, 128 + wn * (NJ / 2) * 32 + j * 32, acc[i][j + NJ / 2][r], acc[i][j + NJ / 2][r + 1],
+                                             acc[i][j + NJ / 2][r + 2], acc[i][j + NJ / 2][r + 3]);
+                                    }
+                            } else {  // EPI_STORE
+#pragma unroll
+                                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                                    for (int g4 = 0; g4 < 4; ++g4) {
+                                        const int r = 4 * g4;
+                                        put4(sb, g4, wn * NJ * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1], acc[i][j][r + 2], acc[i][j][r + 3]);
+                                    }
+                            }
                         }
-                    flush(sb, i, static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
-                } else {  // EPI_STORE
-                    char* sb = next_buf();
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                        for (int g4 = 0; g4 < 4; ++g4) {
-                            const int r = 4 * g4;
-                            put4(sb, g4, wn * NJ * 32 + j * 32, acc[i][j][r], acc[i][j][r + 1], acc[i][j][r + 2], acc[i][j][r + 3]);
-                        }
-                    flush(sb, i, static_cast<bf16_t*>(g.C0), nullptr, 0);
+                        if constexpr (DUAL) flush(sb, i, h, static_cast<bf16_t*>(g.C0), static_cast<bf16_t*>(g.C1), 128);
+                        else flush(sb, i, h, static_cast<bf16_t*>(g.C0), nullptr, 0);
+                    }
                 }
             }
-            __syncthreads();  // the last two passes have been read: the buffer may take the next tile's second stage
+            __syncthreads();  // the last two passes have been read: the chunks under the staging area may be requested
         }
     };
 
     // ================= the tiles of this workgroup =================
-    // Per tile: stages 0 and 1 are in flight when its loop starts (stage 0 was requested before the previous
-    // tile's epilogue, stage 1 after it).  Iteration `it` runs the four k-steps of stage `it`; the barrier in
+    // Per tile: stages 0 and 1 are in flight when its loop starts (both were requested before the previous
+    // tile's epilogue, three chunks of stage 1 after it).  Iteration `it` runs the four k-steps of stage `it`; the barrier in
     // front of the last k-step publishes stage it+1 and frees the buffer of stage it, into which stage it+2 is
     // requested at once: a stage has one whole iteration (about 2 us) to land.
     bf16x8 fa[2][4], fb[2][NJ];
@@ -821,7 +859,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             for (int i = 0; i < NI; ++i) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
                     pin_one(acc[i][j]);
                 }
                 issue_part(it + kStages, it & 1, i * kDeal, (i + 1) * kDeal);
@@ -842,8 +880,10 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             interleave_mfma_dsread<NI * NJ, kReads>();
         }
     };
-    // Stage 0 of the next tile is requested before this tile's epilogue; the epilogue stages through the other buffer.
-    constexpr int kPreStages = 1;
+    // The first two stages of the next tile are requested before this tile's epilogue, all but the chunks
+    // of the second stage buffer that lie under the staging area: wavefront 7 requests those after it.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    constexpr int kEarly = 2 * CPW - kDeferChunks;
     for (;;) {
         const int total = t.nk * g.nseg;
         zero_acc();
@@ -891,11 +931,15 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             di = nt;
             setup_issue();
             ntot = nt.nk * g.nseg;
-            for (int sq = 0; sq < kPreStages && sq < ntot; ++sq) issue(sq, sq);
+            issue(0, 0);
+            if (ntot >= 2) {
+                issue_part(1, 1, 0, kEarly);
+                if (wave_u != kWaves - 1) issue_part(1, 1, kEarly, 2 * CPW);
+            }
         }
-        epilogue(t, smem + kStageBytes);
+        epilogue(t, smem + kStagingOff);
         if (!nt.valid) break;
-        for (int sq = kPreStages; sq < kStages && sq < ntot; ++sq) issue(sq, sq);
+        if (ntot >= 2 && wave_u == kWaves - 1) issue_part(1, 1, kEarly, 2 * CPW);
         t = nt;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -362,7 +362,7 @@ static void launch_gg(const moe_shape* s, const GArgs& g, int64_t R, hipStream_t
         constexpr bool fast_form = RAGK ? (AT == 1 && BT == 0) : (AT == 0);
         if constexpr (fast_form) {
             // (the kernel keeps per-lane offsets in 32 bits; inside a tile they stay below 2^31 bytes)
-            const bool ok = g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8 && g.lda < (1 << 21) && g.ldb < (1 << 21) &&
+            const bool ok = g.lda % 8 == 0 && g.ldb % 8 == 0 && g.N >= 8 && g.lda < (1 << 21) && g.ldb < (1 << 21) && g.ldc < (1 << 22) &&
                             (uint64_t)R * (uint64_t)g.lda < (1ull << 32) && (uint64_t)g.N * (uint64_t)g.ldb < (1ull << 32) &&
                             (RAGK ? (g.M >= 8) : (g.K % TK == 0));
             if (ok) {
