@@ -590,105 +590,121 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
             // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).  Staging rows are 512 B; a lane writes
             // 16-byte pieces of its row, and the piece index is XORed with row%32 so that the 32 rows of a
             // write fall into different banks.
-            // The global operands of a pass (saved A and B, or the old C) are requested before the staging
-            // writes, so that they travel while the accumulators go through LDS.  Every lane loads (dead items
-            // from a clamped address) and every lane consumes what it loaded; only the stores are predicated.
-            // A load skipped or left unconsumed on some path would count as pending at the top of the next
-            // tile's main loop, where the compiler then waits for ALL outstanding loads, the DMA ones included.
-            constexpr int IPT = 64 * 16 / kThreads;  // 8-column items per thread and pass
+            // The arithmetic bounds this epilogue (about 20 VALU issue slots per element, the exponential and
+            // the reciprocal at a quarter of the rate), so nothing else may add to it: the global operands of
+            // pass q+1 (saved A and B, or the old C) are requested at the top of pass q into a second set of
+            // registers and have a whole pass to arrive.  Every lane loads (dead items from a clamped address)
+            // and every lane consumes what it loaded; only the stores are predicated.  The wait for the
+            // operands of pass q leaves the loads of pass q+1 outstanding: vmcnt(loads per pass); loads return in
+            // order, so whatever the stores of pass q-1 do, the older loads have landed when at most the
+            // younger ones are pending.
+            constexpr int IPT = 64 * 16 / kThreads;                  // 8-column items per thread and pass
+            constexpr int NLD = (EPI == EPI_ADD ? 1 : 2) * IPT;      // loads per thread and pass
+            static_assert(NLD == 2 || NLD == 4, "the waits below are written for these counts");
+            const int64_t tile_base = cbase + (int64_t)t.m0 * g.ldc + t.n0;
+            uint32_t ldc_u = (uint32_t)g.ldc;  // (opaque per tile, as in the bf16 path)
+            asm volatile("" : "+s"(ldc_u));
+            const int last_row = t.m_lim - 1 - t.m0, last_col = g.N - 8 - t.n0;
+            u32x4 pre0[2][IPT], pre1[2][IPT];
+            auto load_pass = [&](int q, u32x4 (&p0)[IPT], u32x4 (&p1)[IPT]) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                // (a 128-row tile runs the passes of row blocks 2 and 3 with every item masked: cheaper than
-                // a branch around the pass, which costs the 256-row tiles their load/store overlap)
-                for (int p = 0; p < 2; ++p) {
-                    u32x4 pre0[IPT], pre1[IPT];
-                    int64_t idxs[IPT];
-                    bool live[IPT];
-#pragma unroll
-                    for (int u = 0; u < IPT; ++u) {
-                        const int item = tid + u * kThreads;
-                        const int sr = item >> 4, cg = item & 15;
-                        const int grow = t.m0 + (sr >> 5) * wrows + i * 32 + (sr & 31), gcol = t.n0 + p * 128 + cg * 8;
-                        live[u] = grow < t.m_lim && gcol < g.N && i < ni;
-                        const int lrow = grow < t.m_lim ? grow : t.m_lim - 1, lcol = gcol < g.N ? gcol : g.N - 8;
-                        idxs[u] = (int64_t)grow * g.ldc + gcol;
-                        const int64_t lidx = (int64_t)lrow * g.ldc + lcol;
-                        if constexpr (EPI == EPI_ADD) {
-                            pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.C0) + lidx);
-                            pre1[u] = (u32x4){0, 0, 0, 0};
-                        } else {
-                            pre0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + lidx);
-                            pre1[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + lidx);
-                        }
+                for (int u = 0; u < IPT; ++u) {
+                    const int item = tid + u * kThreads;
+                    const int sr = item >> 4, cg = item & 15;
+                    const int trow = (sr >> 5) * wrows + (q >> 1) * 32 + (sr & 31), tcol = (q & 1) * 128 + cg * 8;
+                    const int lrow = trow < last_row ? trow : last_row, lcol = tcol < last_col ? tcol : last_col;
+                    const uint32_t off = (uint32_t)lrow * ldc_u + (uint32_t)lcol;
+                    if constexpr (EPI == EPI_ADD) {
+                        p0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.C0) + tile_base + off);
+                        p1[u] = (u32x4){0, 0, 0, 0};
+                    } else {
+                        p0[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S0) + tile_base + off);
+                        p1[u] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(g.S1) + tile_base + off);
                     }
-                    {
-                        const int sr = wm * 32 + l32;
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                            for (int g4 = 0; g4 < 4; ++g4) {
-                                const int tcol = wn * NJ * 32 + j * 32 + g4 * 8 + kg * 4;  // column inside the 256-wide tile
-                                const int piece = ((tcol & 127) >> 2) ^ (sr & 31);
-                                if ((tcol >> 7) == p)
-                                    *reinterpret_cast<f32x4v*>(stg + sr * 512 + piece * 16) =
-                                        (f32x4v){acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]};
-                            }
-                    }
-                    __syncthreads();
-                    // vmcnt(0) on every path and visible to the compiler (a builtin, not inline assembly): the
-                    // arithmetic below only feeds predicated stores, so the compiler sinks it, and the wait for
-                    // the loads with it, under the predicate
-                    __builtin_amdgcn_s_waitcnt(0x0F70);
-#pragma unroll
-                    for (int u = 0; u < IPT; ++u) {
-                        const int item = tid + u * kThreads;
-                        const int sr = item >> 4, cg = item & 15;
-                        const int64_t idx = idxs[u];
-                        const int sw = sr & 31;
-                        const f32x4v d0 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg) ^ sw) * 16);
-                        const f32x4v d1 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg + 1) ^ sw) * 16);
-                        const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
-                        if constexpr (EPI == EPI_ADD) {  // C += tile: the bf16 values plus the tile in fp32, one rounding
-                            const u32x4 old = pre0[u];
-                            u32x4 o;
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                const float lo = __uint_as_float(old[q] << 16) + dh[2 * q];
-                                const float hi = __uint_as_float(old[q] & 0xFFFF0000u) + dh[2 * q + 1];
-                                o[q] = pack_bf16x2(lo, hi);
-                            }
-                            if (live[u]) *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = o;
-                        } else {
-                            const u32x4 av = pre0[u], bv = pre1[u];
-                            u32x4 oh, oa, ob;
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                float hh[2], da[2], db[2];
-#pragma unroll
-                                for (int z = 0; z < 2; ++z) {
-                                    const float A = __uint_as_float(z ? (av[q] & 0xFFFF0000u) : (av[q] << 16));
-                                    const float B = __uint_as_float(z ? (bv[q] & 0xFFFF0000u) : (bv[q] << 16));
-                                    const float sg = sigmoid_f(A);             // one exp and one reciprocal per element
-                                    const float sA = A * sg;                   // silu(A)
-                                    const float gr = sg + sA * (1.0f - sg);    // silu'(A) = s (1 + A (1 - s))
-                                    hh[z] = sA * B;
-                                    da[z] = dh[2 * q + z] * B * gr;
-                                    db[z] = dh[2 * q + z] * sA;
-                                }
-                                oh[q] = pack_bf16x2(hh[0], hh[1]);
-                                oa[q] = pack_bf16x2(da[0], da[1]);
-                                ob[q] = pack_bf16x2(db[0], db[1]);
-                            }
-                            if (live[u]) {
-                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = oh;
-                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = oa;
-                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = ob;
-                            }
-                        }
-                    }
-                    __syncthreads();
                 }
+            };
+            // (the number of passes is a compile-time constant of each instance, so that the compiler's
+            // bookkeeping of pending loads is exact and it adds no waits of its own in the next tile's loop)
+            auto run_passes = [&](auto np_tag) {
+            constexpr int NP = decltype(np_tag)::value;
+            load_pass(0, pre0[0], pre1[0]);
+            __builtin_amdgcn_sched_barrier(0);  // the loads of pass 0 stay in front of those of pass 1
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+                const int i = q >> 1, p = q & 1;
+                const bool more = q + 1 < NP;
+                if (more) load_pass(q + 1, pre0[(q + 1) & 1], pre1[(q + 1) & 1]);
+                {
+                    const int sr = wm * 32 + l32;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int g4 = 0; g4 < 4; ++g4) {
+                            const int tcol = wn * NJ * 32 + j * 32 + g4 * 8 + kg * 4;  // column inside the 256-wide tile
+                            const int piece = ((tcol & 127) >> 2) ^ (sr & 31);
+                            if ((tcol >> 7) == p)
+                                *reinterpret_cast<f32x4v*>(stg + sr * 512 + piece * 16) =
+                                    (f32x4v){acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]};
+                        }
+                }
+                __syncthreads();
+                // (builtins, so that the compiler's own bookkeeping of pending loads agrees)
+                if (more) __builtin_amdgcn_s_waitcnt(NLD == 4 ? 0x0F74 : 0x0F72);  // vmcnt(NLD)
+                else __builtin_amdgcn_s_waitcnt(0x0F70);                           // vmcnt(0)
+#pragma unroll
+                for (int u = 0; u < IPT; ++u) {
+                    const int item = tid + u * kThreads;
+                    const int sr = item >> 4, cg = item & 15;
+                    const int trow = (sr >> 5) * wrows + i * 32 + (sr & 31), tcol = p * 128 + cg * 8;
+                    const bool live = t.m0 + trow < t.m_lim && t.n0 + tcol < g.N;
+                    const uint32_t off = (uint32_t)trow * ldc_u + (uint32_t)tcol;
+                    const int sw = sr & 31;
+                    const f32x4v d0 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg) ^ sw) * 16);
+                    const f32x4v d1 = *reinterpret_cast<const f32x4v*>(stg + sr * 512 + ((2 * cg + 1) ^ sw) * 16);
+                    const float dh[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+                    if constexpr (EPI == EPI_ADD) {  // C += tile: the bf16 values plus the tile in fp32, one rounding
+                        const u32x4 old = pre0[q & 1][u];
+                        u32x4 o;
+#pragma unroll
+                        for (int z = 0; z < 4; ++z) {
+                            const float lo = __uint_as_float(old[z] << 16) + dh[2 * z];
+                            const float hi = __uint_as_float(old[z] & 0xFFFF0000u) + dh[2 * z + 1];
+                            o[z] = pack_bf16x2(lo, hi);
+                        }
+                        if (live) *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + tile_base + off) = o;
+                    } else {
+                        const u32x4 av = pre0[q & 1][u], bv = pre1[q & 1][u];
+                        u32x4 oh, oa, ob;
+#pragma unroll
+                        for (int z4 = 0; z4 < 4; ++z4) {
+                            float hh[2], da[2], db[2];
+#pragma unroll
+                            for (int z = 0; z < 2; ++z) {
+                                const float A = __uint_as_float(z ? (av[z4] & 0xFFFF0000u) : (av[z4] << 16));
+                                const float B = __uint_as_float(z ? (bv[z4] & 0xFFFF0000u) : (bv[z4] << 16));
+                                const float sg = sigmoid_f(A);             // one exp and one reciprocal per element
+                                const float sA = A * sg;                   // silu(A)
+                                const float gr = sg + sA * (1.0f - sg);    // silu'(A) = s (1 + A (1 - s))
+                                hh[z] = sA * B;
+                                da[z] = dh[2 * z4 + z] * B * gr;
+                                db[z] = dh[2 * z4 + z] * sA;
+                            }
+                            oh[z4] = pack_bf16x2(hh[0], hh[1]);
+                            oa[z4] = pack_bf16x2(da[0], da[1]);
+                            ob[z4] = pack_bf16x2(db[0], db[1]);
+                        }
+                        if (live) {
+                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + tile_base + off) = oh;
+                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + tile_base + off) = oa;
+                            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + tile_base + off) = ob;
+                        }
+                    }
+                }
+                __syncthreads();
             }
+            };
+            if (ni == 4) run_passes(IntTag<8>{});  // pass q: row block q/2, column half q%2
+            else run_passes(IntTag<4>{});          // (a 128-row tile has two row blocks)
         } else {
             // bf16 tiles: stage [RPP rows][ROWB bytes] with swizzled 16-byte pieces, then 16 bytes per lane along
             // rows.  A pass fills one of two 16 KB areas: block i of both wavefront rows (64 rows of 256 B) or of
