@@ -321,7 +321,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
     // Ragged K: byte offsets relative to the first k-row of the stage (the base moves by scalar adds); only a
     // stage that reaches past the expert's last row forms full per-lane addresses.
     constexpr bool kBDual = DUAL && BT == 0;   // the B tile is two half-width k-row tiles
-    const int b_mat = kBDual ? __builtin_amdgcn_readfirstlane(wave >> 2) : 0;  // the matrix this wavefront's B chunks come from
+    const int b_mat = kBDual ? __builtin_amdgcn_readfirstlane(wave / (kWaves / 2)) : 0;  // the matrix this wavefront's B chunks come from
     uint32_t a_off[CPW], b_off[CPW];
     const char* sA[2];
     const char* sB[2];
