@@ -144,9 +144,9 @@ struct TileDesc {
     bool half;  // ragged M: at most TM/2 live rows (the tail of an expert): computed as a 128 x 256 tile
 };
 
-// The kernel is persistent: one workgroup per CU.  Inside a tile the DMA loads run four k-stages ahead of
-// the MFMAs; the first stages of the next tile are requested before the current tile's epilogue, so they
-// arrive while the epilogue runs (no workgroup relaunch, no cold prologue per tile).
+// The kernel is persistent: one workgroup per CU.  Inside a tile the DMA loads run one k-stage ahead of
+// the MFMAs (two stage buffers); the first two stages of the next tile are requested before the current
+// tile's epilogue, so they arrive while the epilogue runs (no workgroup relaunch, no cold prologue per tile).
 //
 // Which tiles a workgroup runs.  Without GArgs::sched: logical_tile(blockIdx.x + r * gridDim.x), r = 0, 1, ...
 // With it: the logical tile order is cut into blocks of 32, block b belongs to the queue of XCD b % 8, and
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
         return t;
     };
 
-    // ================= issue side: DMA loads of stream position p into ring buffer p & 3 =================
+    // ================= issue side: DMA loads of k-stage s into stage buffer s & 1 =================
     const int64_t lda = g.lda, ldb = g.ldb;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * (CPW * 1024));
