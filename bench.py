@@ -221,7 +221,7 @@ def run_workload(w, steps, warmup, inp=None, keep=False):
     if inp is None:
         inp = I.layer_inputs(w)
     g = {n: (to_device(v, dt) if n != "bias" else torch.from_numpy(v).cuda()) for n, v in inp.items()}
-    buf = MoeLayerBuffers(s, backward=w.backward)
+    buf = MoeLayerBuffers(s, backward=w.backward, save_products=SAVED_AS == "products")
     torch.cuda.synchronize()
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -237,13 +237,11 @@ def run_workload(w, steps, warmup, inp=None, keep=False):
         B.moe_gate_topk(s, g["x"], g["w_gate"], g["bias"], buf.topk_ids, buf.topk_w, None, buf.ws); mark(1)
         B.moe_permute(s, g["x"], buf.topk_ids, buf.counts, buf.offsets, buf.row_of_pair, buf.pair_of_row,
                       buf.x_perm, buf.ws); mark(2)
-        B.moe_grouped_ffn_fwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.y_perm, buf.a_save,
-                              buf.b_save, buf.ws); mark(3)
+        buf.ffn_fwd(g["w1"], g["w3"], g["w2"]); mark(3)
         B.moe_unpermute_combine(s, buf.y_perm, buf.row_of_pair, buf.topk_w, buf.y); mark(4)
         if w.backward:
             B.moe_combine_bwd(s, g["dy"], buf.y_perm, buf.row_of_pair, buf.topk_w, buf.dy_perm, buf.dtopk_w); mark(5)
-            B.moe_grouped_ffn_bwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.a_save, buf.b_save,
-                                  buf.dy_perm, buf.dx_perm, buf.dw1, buf.dw3, buf.dw2, buf.ws); mark(6)
+            buf.ffn_bwd(g["w1"], g["w3"], g["w2"]); mark(6)
             B.moe_unpermute_combine(s, buf.dx_perm, buf.row_of_pair, None, buf.dx); mark(7)
             B.moe_gate_topk_bwd(s, g["x"], g["w_gate"], buf.topk_ids, buf.topk_w, buf.dtopk_w, buf.dx,
                                 buf.dw_gate, buf.ws); mark(8)
@@ -360,15 +358,22 @@ def ceilings_leg():
     return out
 
 
+# What the forward pass keeps for the backward pass: "ab" = A and B (moe_grouped_ffn_fwd/_bwd), "products" = H,
+# B*silu'(A) and silu(A) (moe_grouped_ffn_fwd_products/_bwd_products: one more saved tensor, a cheaper backward)
+SAVED_AS = "ab"
+
 OTHER_WORKLOADS = ["cfg2_e64k4", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced"]
 
 
 def main():
+    global SAVED_AS
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3_mixtral")
+    ap.add_argument("--saved", choices=["ab", "products"], default=SAVED_AS,
+                    help="what the forward pass keeps for the backward pass (see SAVED_AS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short runs of the other configurations (other_workloads)")
@@ -378,6 +383,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
+    SAVED_AS = args.saved
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the hot path of one device's token share); "
               "--gpus must be 1", file=sys.stderr)

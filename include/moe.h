@@ -36,8 +36,8 @@
  *     moe_last_error().  Data-dependent faults (non-finite values, expert ids
  *     out of range, offsets that do not describe R rows) are undefined
  *     behaviour and are not checked on the device.
- *   - Device: the grouped-GEMM calls (moe_grouped_ffn_fwd, _fwd_groups, _bwd and, for bf16,
- *     moe_gate_topk_bwd) are laid out for a whole MI355X (gfx950, 256 compute units: one persistent
+ *   - Device: the grouped-GEMM calls (moe_grouped_ffn_fwd, _fwd_groups, _fwd_products, _bwd, _bwd_groups,
+ *     _bwd_products and, for bf16, moe_gate_topk_bwd) are laid out for a whole MI355X (gfx950, 256 compute units: one persistent
  *     workgroup per unit, dealt round-robin to the 8 XCDs).  They look the current device up once and
  *     return MOE_ERR_UNSUPPORTED on any other architecture or under a compute-unit mask, and
  *     MOE_ERR_DEVICE if no device can be queried; nothing is launched in either case.  One-time kernel
@@ -209,6 +209,24 @@ moe_status moe_grouped_ffn_bwd(const moe_shape* shape, const void* x_perm, const
                                const void* b_save, const void* dy_perm, void* dx_perm /*[R,d]*/,
                                void* dw1, void* dw3, void* dw2, void* ws, size_t ws_bytes,
                                void* stream);
+
+/* The same pair of calls with the activations saved as products (section 3.1: the SwiGLU expert;
+ * section 3.2: backward priced at twice the forward).  What the backward pass needs of A and B is
+ *   H = silu(A) (.) B  (for dw2),   P = B (.) silu'(A)  (dA = dH (.) P),   Q = silu(A)  (dB = dH (.) Q),
+ * so the forward call keeps H (which it computes anyway) and writes P and Q where the plain call writes A
+ * and B: h_save, p_save, q_save [R,f] el, all required.  The backward call then spends two multiplications
+ * per element where the plain one recomputes a sigmoid, at the price of a third saved tensor.  P and Q are
+ * rounded to el once; everything else as in moe_grouped_ffn_fwd / moe_grouped_ffn_bwd.
+ * Workspace: none in the forward call; the backward call uses it (dA, dB), size as for moe_grouped_ffn_bwd. */
+moe_status moe_grouped_ffn_fwd_products(const moe_shape* shape, const void* x_perm, const int32_t* offsets,
+                                        const void* w1, const void* w3, const void* w2,
+                                        void* y_perm /*[R,d] el*/, void* h_save, void* p_save, void* q_save,
+                                        void* stream);
+moe_status moe_grouped_ffn_bwd_products(const moe_shape* shape, const void* x_perm, const int32_t* offsets,
+                                        const void* w1, const void* w3, const void* w2, const void* h_save,
+                                        const void* p_save, const void* q_save, const void* dy_perm,
+                                        void* dx_perm /*[R,d]*/, void* dw1, void* dw3, void* dw2, void* ws,
+                                        size_t ws_bytes, void* stream);
 
 /* Weighted combine ("a weighted sum of the outputs from the selected experts",
  * introduction; the mixture formula of the Preliminary section).

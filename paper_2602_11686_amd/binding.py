@@ -25,7 +25,8 @@ EXPORTS = [
     "moe_status_string", "moe_last_error", "moe_abi_version", "moe_workspace_bytes", "moe_gate_topk",
     "moe_permute", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_combine_bwd",
     "moe_gate_topk_bwd", "moe_permute_lite", "moe_grouped_ffn_fwd_groups", "moe_permute_static",
-    "moe_permute_static_max_hist_entries", "moe_grouped_ffn_bwd_groups",
+    "moe_permute_static_max_hist_entries", "moe_grouped_ffn_bwd_groups", "moe_grouped_ffn_fwd_products",
+    "moe_grouped_ffn_bwd_products",
 ]
 _NOT_A_STATUS = {"moe_status_string", "moe_last_error", "moe_abi_version", "moe_workspace_bytes",
                  "moe_permute_static_max_hist_entries"}
@@ -212,6 +213,40 @@ def moe_grouped_ffn_fwd_groups(s: Shape, G: int, expert_of_group, x_perm, group_
                                             _ptr(a_save, s.dtype, (s.R, s.f), "a_save"),
                                             _ptr(b_save, s.dtype, (s.R, s.f), "b_save"), wp, wn, _stream()),
            "moe_grouped_ffn_fwd_groups")
+
+
+def moe_grouped_ffn_fwd_products(s: Shape, x_perm, offsets, w1, w3, w2, y_perm, h_save, p_save, q_save):
+    c = s.c()
+    _check(lib().moe_grouped_ffn_fwd_products(ctypes.byref(c), _ptr(x_perm, s.dtype, (s.R, s.d), "x_perm"),
+                                              _ptr(offsets, torch.int32, (s.E + 1,), "offsets"),
+                                              _ptr(w1, s.dtype, (s.E, s.d, s.f), "w1"),
+                                              _ptr(w3, s.dtype, (s.E, s.d, s.f), "w3"),
+                                              _ptr(w2, s.dtype, (s.E, s.f, s.d), "w2"),
+                                              _ptr(y_perm, s.dtype, (s.R, s.d), "y_perm"),
+                                              _ptr(h_save, s.dtype, (s.R, s.f), "h_save"),
+                                              _ptr(p_save, s.dtype, (s.R, s.f), "p_save"),
+                                              _ptr(q_save, s.dtype, (s.R, s.f), "q_save"), _stream()),
+           "moe_grouped_ffn_fwd_products")
+
+
+def moe_grouped_ffn_bwd_products(s: Shape, x_perm, offsets, w1, w3, w2, h_save, p_save, q_save, dy_perm, dx_perm,
+                                 dw1, dw3, dw2, ws):
+    c = s.c()
+    wp, wn = _ws(ws)
+    _check(lib().moe_grouped_ffn_bwd_products(ctypes.byref(c), _ptr(x_perm, s.dtype, (s.R, s.d), "x_perm"),
+                                              _ptr(offsets, torch.int32, (s.E + 1,), "offsets"),
+                                              _ptr(w1, s.dtype, (s.E, s.d, s.f), "w1"),
+                                              _ptr(w3, s.dtype, (s.E, s.d, s.f), "w3"),
+                                              _ptr(w2, s.dtype, (s.E, s.f, s.d), "w2"),
+                                              _ptr(h_save, s.dtype, (s.R, s.f), "h_save"),
+                                              _ptr(p_save, s.dtype, (s.R, s.f), "p_save"),
+                                              _ptr(q_save, s.dtype, (s.R, s.f), "q_save"),
+                                              _ptr(dy_perm, s.dtype, (s.R, s.d), "dy_perm"),
+                                              _ptr(dx_perm, s.dtype, (s.R, s.d), "dx_perm"),
+                                              _ptr(dw1, s.dtype, (s.E, s.d, s.f), "dw1"),
+                                              _ptr(dw3, s.dtype, (s.E, s.d, s.f), "dw3"),
+                                              _ptr(dw2, s.dtype, (s.E, s.f, s.d), "dw2"), wp, wn, _stream()),
+           "moe_grouped_ffn_bwd_products")
 
 
 def moe_grouped_ffn_bwd(s: Shape, x_perm, offsets, w1, w3, w2, a_save, b_save, dy_perm, dx_perm, dw1, dw3, dw2, ws):

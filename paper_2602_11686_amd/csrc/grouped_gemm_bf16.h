@@ -585,11 +585,13 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                             if (col + z < g.N) d[z] = acc[i][j][4 * g4 + z];
                     }
             }
-        } else if constexpr (EPI == EPI_DH || EPI == EPI_ADD) {
+        } else if constexpr (EPI == EPI_DH || EPI == EPI_DHP || EPI == EPI_ADD) {
             // dH in fp32 through LDS, 64 rows x 128 columns at a time; then 8 columns per thread: read A, B,
             // write H = silu(A)*B, dA = dH*B*silu'(A), dB = dH*silu(A).  Staging rows are 512 B; a lane writes
             // 16-byte pieces of its row, and the piece index is XORed with row%32 so that the 32 rows of a
             // write fall into different banks.
+            // EPI_DHP is the same epilogue for activations saved as products (P = B*silu'(A), Q = silu(A); H is
+            // saved too and not rewritten): dA = dH*P, dB = dH*Q, two multiplications per element.
             // The arithmetic bounds this epilogue (about 20 VALU issue slots per element, the exponential and
             // the reciprocal at a quarter of the rate), so nothing else may add to it: the global operands of
             // pass q+1 (saved A and B, or the old C) are requested at the top of pass q into a second set of
@@ -675,6 +677,20 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
                     } else {
                         const u32x4 av = pre0[q & 1][u], bv = pre1[q & 1][u];
                         u32x4 oh, oa, ob;
+                        if constexpr (EPI == EPI_DHP) {
+#pragma unroll
+                            for (int z4 = 0; z4 < 4; ++z4) {
+                                const float p_lo = __uint_as_float(av[z4] << 16), p_hi = __uint_as_float(av[z4] & 0xFFFF0000u);
+                                const float q_lo = __uint_as_float(bv[z4] << 16), q_hi = __uint_as_float(bv[z4] & 0xFFFF0000u);
+                                oa[z4] = pack_bf16x2(dh[2 * z4] * p_lo, dh[2 * z4 + 1] * p_hi);
+                                ob[z4] = pack_bf16x2(dh[2 * z4] * q_lo, dh[2 * z4 + 1] * q_hi);
+                            }
+                            if (live) {
+                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + tile_base + off) = oa;
+                                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + tile_base + off) = ob;
+                            }
+                            continue;
+                        }
 #pragma unroll
                         for (int z4 = 0; z4 < 4; ++z4) {
                             float hh[2], da[2], db[2];
@@ -773,7 +789,14 @@ __global__ __launch_bounds__(kThreads) void gg256_kernel(const GArgs g) {
 #pragma unroll
                                 for (int z = 0; z < 4; ++z) {
                                     const float a = acc[i][j][4 * g4 + z], b = acc[i][j + NJ / 2][4 * g4 + z];
-                                    v[z] = pass == 0 ? silu_f(a) * b : pass == 1 ? a : b;
+                                    if (pass == 0) {
+                                        v[z] = silu_f(a) * b;
+                                    } else if (!g.products) {
+                                        v[z] = pass == 1 ? a : b;
+                                    } else {  // P = b * silu'(a), Q = silu(a)
+                                        const float sg = sigmoid_f(a), sA = a * sg;
+                                        v[z] = pass == 1 ? b * (sg + sA * (1.0f - sg)) : sA;
+                                    }
                                 }
                                 put4(sb, g4, wn * (NJ / 2) * 32 + j * 32, v[0], v[1], v[2], v[3]);
                             }

@@ -29,7 +29,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-enum { EPI_STORE = 0, EPI_STORE2 = 1, EPI_SWIGLU = 2, EPI_DH = 3, EPI_STORE_F32 = 4, EPI_ADD = 5 };
+enum { EPI_STORE = 0, EPI_STORE2 = 1, EPI_SWIGLU = 2, EPI_DH = 3, EPI_STORE_F32 = 4, EPI_ADD = 5, EPI_DHP = 6 };
 
 struct Seg {
     const void* A;
@@ -51,6 +51,7 @@ struct GArgs {
     void* C2;
     const void* S0;        // saved A (EPI_DH: read; EPI_SWIGLU: written if non-null)
     const void* S1;        // saved B
+    int products;          // the saved pair is P = B*silu'(A), Q = silu(A) instead of A, B (EPI_SWIGLU writes it, EPI_DHP reads it)
     int64_t ldc;
     const int32_t* order;  // ragged K: experts by row count, heaviest first (may be null)
     const void* zero_row;  // ragged K: 512 bytes of zeros in device memory
@@ -78,9 +79,14 @@ __device__ __forceinline__ void epilogue_elem(const GArgs& g, int64_t idx, float
     } else if constexpr (EPI == EPI_SWIGLU) {
         Elem<T>::store(static_cast<T*>(g.C0) + idx, silu_f(a) * b);
         if (g.S0) {
-            Elem<T>::store(const_cast<T*>(static_cast<const T*>(g.S0)) + idx, a);
-            Elem<T>::store(const_cast<T*>(static_cast<const T*>(g.S1)) + idx, b);
+            Elem<T>::store(const_cast<T*>(static_cast<const T*>(g.S0)) + idx, g.products ? b * silu_grad_f(a) : a);
+            Elem<T>::store(const_cast<T*>(static_cast<const T*>(g.S1)) + idx, g.products ? silu_f(a) : b);
         }
+    } else if constexpr (EPI == EPI_DHP) {  // a = dH; saved P, Q
+        const float P = Elem<T>::load(static_cast<const T*>(g.S0) + idx);
+        const float Q = Elem<T>::load(static_cast<const T*>(g.S1) + idx);
+        Elem<T>::store(static_cast<T*>(g.C1) + idx, a * P);
+        Elem<T>::store(static_cast<T*>(g.C2) + idx, a * Q);
     } else {  // EPI_DH: a = dH
         const float A = Elem<T>::load(static_cast<const T*>(g.S0) + idx);
         const float B = Elem<T>::load(static_cast<const T*>(g.S1) + idx);
@@ -440,20 +446,21 @@ using namespace moe;
 // are those of expert expert_of_group[g])
 static void run_fwd1(const moe_shape* s, const void* x_perm, const int32_t* offsets, const void* w1, const void* w3,
                      void* H, void* a_save, void* b_save, hipStream_t st, int groups = 0,
-                     const int32_t* expert_of_group = nullptr) {
+                     const int32_t* expert_of_group = nullptr, bool products = false) {
     GArgs g{};
     g.offsets = offsets; g.E = groups ? groups : s->E; g.N = s->f; g.K = s->d; g.nseg = 1;
     g.expert_of_group = expert_of_group; g.n_weights = s->E;
     g.seg[0] = {x_perm, w1, w3};
     g.lda = s->d; g.ldb = s->f; g.strideB = (int64_t)s->d * s->f;
-    g.C0 = H; g.S0 = a_save; g.S1 = b_save; g.ldc = s->f;
+    g.C0 = H; g.S0 = a_save; g.S1 = b_save; g.ldc = s->f; g.products = products ? 1 : 0;
     launch_gg<0, 0, true, EPI_SWIGLU, false>(s, g, (int64_t)s->T * s->k, st);
 }
 
 static moe_status ffn_fwd_impl(const char* who, const moe_shape* s, int groups, const int32_t* expert_of_group,
                                const void* x_perm, const int32_t* offsets, const void* w1, const void* w3,
                                const void* w2, void* y_perm, void* a_save, void* b_save, void* ws, size_t ws_bytes,
-                               void* stream) {
+                               void* stream, void* h_save = nullptr) {
+    // h_save: the products form (H is kept, the saved pair is P = B*silu'(A), Q = silu(A)); no workspace then
     MOE_RETURN_IF(check_shape(s, who));
     MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who));
     MOE_RETURN_IF(check_ptr(offsets, "offsets", who));
@@ -463,20 +470,20 @@ static moe_status ffn_fwd_impl(const char* who, const moe_shape* s, int groups, 
     MOE_RETURN_IF(check_ptr(y_perm, "y_perm", who));
     MOE_RETURN_IF(check_ptr(a_save, "a_save", who, true));
     MOE_RETURN_IF(check_ptr(b_save, "b_save", who, true));
-    MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    if (!h_save) MOE_RETURN_IF(check_ptr(ws, "ws", who));
     if ((a_save == nullptr) != (b_save == nullptr)) {
         set_error("%s: a_save and b_save must both be given or both be NULL", who);
         return MOE_ERR_INVALID_ARG;
     }
     MOE_RETURN_IF(check_device(who));
-    if (ws_bytes < ffn_fwd_workspace_bytes(s)) {
+    if (!h_save && ws_bytes < ffn_fwd_workspace_bytes(s)) {
         set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, ffn_fwd_workspace_bytes(s));
         return MOE_ERR_WORKSPACE_TOO_SMALL;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t R = (int64_t)s->T * s->k;
-    void* H = ws;
-    run_fwd1(s, x_perm, offsets, w1, w3, H, a_save, b_save, st, groups, expert_of_group);
+    void* H = h_save ? h_save : ws;
+    run_fwd1(s, x_perm, offsets, w1, w3, H, a_save, b_save, st, groups, expert_of_group, h_save != nullptr);
     GArgs g{};
     g.offsets = offsets; g.E = groups; g.N = s->d; g.K = s->f; g.nseg = 1;
     g.expert_of_group = expert_of_group; g.n_weights = s->E;
@@ -513,7 +520,7 @@ static moe_status ffn_bwd_impl(const char* who, const moe_shape* s, int groups, 
                                const void* x_perm, const int32_t* offsets, const void* w1, const void* w3,
                                const void* w2, const void* a_save, const void* b_save, const void* dy_perm,
                                void* dx_perm, void* dw1, void* dw3, void* dw2, void* ws, size_t ws_bytes,
-                               void* stream) {
+                               void* stream, const void* h_save = nullptr) {
     MOE_RETURN_IF(check_shape(s, who));
     MOE_RETURN_IF(check_ptr(x_perm, "x_perm", who));
     MOE_RETURN_IF(check_ptr(offsets, "offsets", who));
@@ -528,6 +535,10 @@ static moe_status ffn_bwd_impl(const char* who, const moe_shape* s, int groups, 
     MOE_RETURN_IF(check_ptr(dw3, "dw3", who));
     MOE_RETURN_IF(check_ptr(dw2, "dw2", who));
     MOE_RETURN_IF(check_ptr(ws, "ws", who));
+    if (h_save && (!a_save || !b_save)) {
+        set_error("%s: the products form needs h_save, p_save and q_save", who);
+        return MOE_ERR_INVALID_ARG;
+    }
     MOE_RETURN_IF(check_device(who));
     if (ws_bytes < ffn_bwd_workspace_bytes(s)) {
         set_error("%s: workspace %zu < %zu bytes", who, ws_bytes, ffn_bwd_workspace_bytes(s));
@@ -537,7 +548,7 @@ static moe_status ffn_bwd_impl(const char* who, const moe_shape* s, int groups, 
     const int64_t R = (int64_t)s->T * s->k;
     const size_t rf = (size_t)R * s->f * el_size(s);
     Carver cv(ws);
-    void* H = cv.take(rf);
+    void* H = cv.take(rf);  // (not used in the products form, which reads h_save)
     void* dA = cv.take(rf);
     void* dB = cv.take(rf);
     int32_t* order = static_cast<int32_t*>(cv.take(1024));
@@ -559,7 +570,8 @@ static moe_status ffn_bwd_impl(const char* who, const moe_shape* s, int groups, 
         g.seg[0] = {dy_perm, w2, nullptr};
         g.lda = s->d; g.ldb = s->d; g.strideB = (int64_t)s->f * s->d;
         g.C0 = H; g.C1 = dA; g.C2 = dB; g.S0 = a_save; g.S1 = b_save; g.ldc = s->f;
-        launch_gg<0, 1, false, EPI_DH, false>(s, g, R, st);
+        if (h_save) launch_gg<0, 1, false, EPI_DHP, false>(s, g, R, st);  // dA = dH*P, dB = dH*Q
+        else launch_gg<0, 1, false, EPI_DH, false>(s, g, R, st);
     }
     {  // dXp = dA * W1^T + dB * W3^T
         GArgs g{};
@@ -574,7 +586,7 @@ static moe_status ffn_bwd_impl(const char* who, const moe_shape* s, int groups, 
     {  // dW2[e] = H_e^T * dYp_e
         GArgs g{};
         g.offsets = offsets; g.E = groups; g.M = s->f; g.N = s->d; g.nseg = 1;
-        g.seg[0] = {H, dy_perm, nullptr};
+        g.seg[0] = {h_save ? h_save : H, dy_perm, nullptr};
         g.lda = s->f; g.ldb = s->d; g.strideC = (int64_t)s->f * s->d;
         g.C0 = dw2; g.ldc = s->d; g.order = order; g.zero_row = zero_row;
         g.sched = sched;
@@ -599,6 +611,30 @@ extern "C" moe_status moe_grouped_ffn_bwd(const moe_shape* s, const void* x_perm
                                           void* dw2, void* ws, size_t ws_bytes, void* stream) {
     return ffn_bwd_impl("moe_grouped_ffn_bwd", s, s ? s->E : 0, nullptr, x_perm, offsets, w1, w3, w2, a_save, b_save,
                         dy_perm, dx_perm, dw1, dw3, dw2, ws, ws_bytes, stream);
+}
+
+extern "C" moe_status moe_grouped_ffn_fwd_products(const moe_shape* s, const void* x_perm, const int32_t* offsets,
+                                                   const void* w1, const void* w3, const void* w2, void* y_perm,
+                                                   void* h_save, void* p_save, void* q_save, void* stream) {
+    const char* who = "moe_grouped_ffn_fwd_products";
+    MOE_RETURN_IF(check_ptr(h_save, "h_save", who));
+    MOE_RETURN_IF(check_ptr(p_save, "p_save", who));
+    MOE_RETURN_IF(check_ptr(q_save, "q_save", who));
+    return ffn_fwd_impl(who, s, s ? s->E : 0, nullptr, x_perm, offsets, w1, w3, w2, y_perm, p_save, q_save, nullptr, 0,
+                        stream, h_save);
+}
+
+extern "C" moe_status moe_grouped_ffn_bwd_products(const moe_shape* s, const void* x_perm, const int32_t* offsets,
+                                                   const void* w1, const void* w3, const void* w2, const void* h_save,
+                                                   const void* p_save, const void* q_save, const void* dy_perm,
+                                                   void* dx_perm, void* dw1, void* dw3, void* dw2, void* ws,
+                                                   size_t ws_bytes, void* stream) {
+    const char* who = "moe_grouped_ffn_bwd_products";
+    MOE_RETURN_IF(check_ptr(h_save, "h_save", who));
+    MOE_RETURN_IF(check_ptr(p_save, "p_save", who));
+    MOE_RETURN_IF(check_ptr(q_save, "q_save", who));
+    return ffn_bwd_impl(who, s, s ? s->E : 0, nullptr, x_perm, offsets, w1, w3, w2, p_save, q_save, dy_perm, dx_perm,
+                        dw1, dw3, dw2, ws, ws_bytes, stream, h_save);
 }
 
 extern "C" moe_status moe_grouped_ffn_bwd_groups(const moe_shape* s, int32_t G, const int32_t* expert_of_group,

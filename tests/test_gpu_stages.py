@@ -183,6 +183,51 @@ def test_grouped_ffn_bwd(case):
                 and float(buf.dw3[e].abs().max()) == 0
 
 
+def test_grouped_ffn_products(case):
+    """The pair of calls that saves H, P = B*silu'(A) and Q = silu(A): same outputs as the plain pair, the saved
+    tensors against the oracle's A and B put through scipy's expit, the gradients against the oracle's."""
+    from scipy.special import expit
+    w, inp, o, fw, bw, g = case
+    if not w.backward:
+        pytest.skip("forward-only configuration")
+    s = shape_of(w)
+    buf = MoeLayerBuffers(s, backward=True)
+    xp = dev(round_like(fw["Xp"], w), w)
+    off = torch.from_numpy(fw["offsets"]).cuda()
+    tol = TOL[tdtype(w)]
+    h, p, q = (torch.full_like(buf.a_save, float("nan")) for _ in range(3))
+    y = torch.full_like(buf.y_perm, float("nan"))
+    B.moe_grouped_ffn_fwd_products(s, xp, off, g["w1"], g["w3"], g["w2"], y, h, p, q)
+    B.moe_grouped_ffn_fwd(s, xp, off, g["w1"], g["w3"], g["w2"], buf.y_perm, None, None, buf.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y, buf.y_perm)
+    A, Bm = fw["A"].astype(np.float64), fw["B"].astype(np.float64)
+    sg = expit(A)
+    groups = row_blocks(fw["offsets"])
+    for name, got, want in (("H", h, A * sg * Bm), ("P", p, Bm * sg * (1.0 + A * (1.0 - sg))), ("Q", q, A * sg)):
+        got = host(got)
+        assert rel_max(got, want) <= tol, name
+        err, e = rel_max_blocks(got, want, groups)
+        assert err <= tol, (name, "expert", e, err)
+    dyp_stored = round_like(bw["dYp"], w)
+    ref = O.ffn_bwd(fw["Xp"], fw["offsets"], o["w1"], o["w3"], o["w2"], I.widen(dyp_stored, np.float64))
+    for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
+        t.fill_(float("nan"))
+    B.moe_grouped_ffn_bwd_products(s, xp, off, g["w1"], g["w3"], g["w2"], h, p, q, dev(dyp_stored, w), buf.dx_perm,
+                                   buf.dw1, buf.dw3, buf.dw2, buf.ws)
+    torch.cuda.synchronize()
+    for name, got, want in (("dXp", buf.dx_perm, ref[0]), ("dW1", buf.dw1, ref[1]), ("dW3", buf.dw3, ref[2]),
+                            ("dW2", buf.dw2, ref[3])):
+        got = host(got)
+        assert rel_max(got, want) <= tol, name
+        blocks = groups if name == "dXp" else range(w.E)
+        err, e = rel_max_blocks(got, want, blocks)
+        assert err <= tol, (name, "expert", e, err)
+    for e in np.nonzero(fw["counts"] == 0)[0]:
+        assert float(buf.dw1[e].abs().max()) == 0 and float(buf.dw2[e].abs().max()) == 0 \
+            and float(buf.dw3[e].abs().max()) == 0
+
+
 def test_gate_topk_bwd(case):
     w, inp, o, fw, bw, g = case
     s = shape_of(w)
