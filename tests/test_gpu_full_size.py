@@ -211,15 +211,11 @@ def test_grouped_ffn_backward_sampled(case):
     for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
         assert bool(torch.isfinite(t).all())
     tol = TOL[tdtype(w)]
-    # (1) whole rows of dXp
+    # oracle samples: (1) whole rows of dXp, (2) weight gradients on a subset J of the intermediate channels,
+    # over all rows
     rows = case.sample_rows(24 if w.d * w.f > 2 ** 24 else 96)
     dyp_rows = host(dyp[torch.from_numpy(rows).cuda()]).astype(np.float32)
     _, dxp_ref = case.oracle_ffn_rows(rows, dyp_rows)
-    dxp_gpu = host(buf.dx_perm[torch.from_numpy(rows).cuda()])
-    assert rel_max(dxp_gpu, dxp_ref) <= tol
-    err, b = rel_max_blocks(dxp_gpu, dxp_ref, case.sample_blocks(rows))
-    assert err <= tol, ("dXp", "expert block", b, err)
-    # (2) weight gradients on a subset J of the intermediate channels, over all rows
     print(f"[full-size] {w.name}: oracle wgrad on a channel subset", flush=True)
     nJ = 16 if w.d * w.f > 2 ** 24 else 48
     J = np.unique(np.concatenate([[0, w.f - 1], case.rng.integers(0, w.f, nJ)]))
@@ -232,16 +228,24 @@ def test_grouped_ffn_backward_sampled(case):
     Jt = torch.from_numpy(J).cuda()
     light = np.argsort(case.counts)[: min(w.E, 8)]
     print(f"[full-size] {w.name}: lightest experts have {case.counts[light].tolist()} rows", flush=True)
-    for name, got, want in (("dW1", buf.dw1[:, :, Jt], dW1), ("dW3", buf.dw3[:, :, Jt], dW3),
-                            ("dW2", buf.dw2[:, Jt, :], dW2)):
-        got = host(got)
-        assert rel_max(got, want) <= tol, name
-        # every expert's gradient block against that expert's own scale (the lightest experts included)
-        err, e = rel_max_blocks(got, want, range(w.E))
-        assert err <= tol, (name, "expert", e, "rows", int(case.counts[e]), err)
-    for e in np.nonzero(case.counts == 0)[0]:
-        assert float(buf.dw1[e].abs().max()) == 0 and float(buf.dw3[e].abs().max()) == 0 \
-            and float(buf.dw2[e].abs().max()) == 0
+
+    def check(form):
+        dxp_gpu = host(buf.dx_perm[torch.from_numpy(rows).cuda()])
+        assert rel_max(dxp_gpu, dxp_ref) <= tol, form
+        err, b = rel_max_blocks(dxp_gpu, dxp_ref, case.sample_blocks(rows))
+        assert err <= tol, (form, "dXp", "expert block", b, err)
+        for name, got, want in (("dW1", buf.dw1[:, :, Jt], dW1), ("dW3", buf.dw3[:, :, Jt], dW3),
+                                ("dW2", buf.dw2[:, Jt, :], dW2)):
+            got = host(got)
+            assert rel_max(got, want) <= tol, (form, name)
+            # every expert's gradient block against that expert's own scale (the lightest experts included)
+            err, e = rel_max_blocks(got, want, range(w.E))
+            assert err <= tol, (form, name, "expert", e, "rows", int(case.counts[e]), err)
+        for e in np.nonzero(case.counts == 0)[0]:
+            assert float(buf.dw1[e].abs().max()) == 0 and float(buf.dw3[e].abs().max()) == 0 \
+                and float(buf.dw2[e].abs().max()) == 0
+
+    check("A and B saved")
     # (3) the recomputing variant gives the same gradients bit for bit
     ref = [t.clone() for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2)]
     B.moe_grouped_ffn_bwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], None, None, dyp,
@@ -249,6 +253,21 @@ def test_grouped_ffn_backward_sampled(case):
     torch.cuda.synchronize()
     for a, b in zip(ref, (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2)):
         assert torch.equal(a, b)
+    # (4) the pair of calls that saves H, B*silu'(A) and silu(A): the same samples
+    del ref
+    h_save = torch.empty_like(buf.a_save)
+    y2 = torch.empty_like(buf.y_perm)
+    B.moe_grouped_ffn_fwd_products(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], y2, h_save, buf.a_save,
+                                   buf.b_save)
+    assert torch.equal(y2, buf.y_perm)
+    for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
+        t.fill_(float("nan"))
+    B.moe_grouped_ffn_bwd_products(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], h_save, buf.a_save,
+                                   buf.b_save, dyp, buf.dx_perm, buf.dw1, buf.dw3, buf.dw2, buf.ws)
+    torch.cuda.synchronize()
+    for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
+        assert bool(torch.isfinite(t).all())
+    check("products saved")
 
 
 @pytest.mark.parametrize("T,k,E", [(280_000, 8, 200), (150_001, 3, 7)])
