@@ -87,6 +87,17 @@ def test_grouped_gemm_calls_refuse_to_run_without_a_supported_device():
     # argument errors still come first
     st = L.moe_grouped_ffn_fwd(ctypes.byref(c), None, p, p, p, p, p, None, None, p, big, None)
     assert st == 1
+    # the pair that saves products: all three saved tensors are required; no workspace in the forward call
+    st = L.moe_grouped_ffn_fwd_products(ctypes.byref(c), p, p, p, p, p, p, p, p, p, None)
+    assert st == 4 and b"GPU" in L.moe_last_error()
+    st = L.moe_grouped_ffn_fwd_products(ctypes.byref(c), p, p, p, p, p, p, p, None, p, None)
+    assert st == 1 and b"p_save" in L.moe_last_error()
+    st = L.moe_grouped_ffn_bwd_products(ctypes.byref(c), p, p, p, p, p, p, p, p, p, p, p, p, p, p, big, None)
+    assert st == 4
+    st = L.moe_grouped_ffn_bwd_products(ctypes.byref(c), p, p, p, p, p, None, p, p, p, p, p, p, p, p, big, None)
+    assert st == 1 and b"h_save" in L.moe_last_error()
+    st = L.moe_grouped_ffn_bwd_products(ctypes.byref(c), p, p, p, p, p, p, p, p, p, p, p, p, p, p, ctypes.c_size_t(8), None)
+    assert st in (3, 4)   # (the workspace check sits behind the device check)
 
 
 def test_one_time_kernel_attributes_are_set_under_a_lock():

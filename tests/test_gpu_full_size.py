@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of the workloads, in the launch configuration bench.py times.
 
 The oracle cannot run a whole Mixtral-sized layer in a test, so at full size
   * the gate and the permutation are compared in full (integer outputs bit-exact),
@@ -268,6 +268,59 @@ def test_grouped_ffn_backward_sampled(case):
     for t in (buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
         assert bool(torch.isfinite(t).all())
     check("products saved")
+
+
+def test_backward_over_two_groups_per_expert(case):
+    """A property that holds at any size: cut every expert's rows into two replica groups (G = 2E, the second
+    group may be empty).  The layer output and dXp are per-row results and must keep their bits; the two groups'
+    weight gradients add up to the expert's (each is rounded to the storage type once, so the sum sits within
+    the bar of the plain gradient, expert by expert)."""
+    w, s, g = case.w, case.s, case.g
+    if not w.backward or 2 * w.E > 256 or w.name not in ("cfg3_mixtral", "cfg4_finegrained", "mixtral8x7b_e16k4"):
+        pytest.skip("run on three backward workloads with 2E <= 256")
+    buf = MoeLayerBuffers(s, backward=True)
+    ids = torch.from_numpy(case.ids).cuda()
+    B.moe_permute(s, g["x"], ids, buf.counts, buf.offsets, buf.row_of_pair, buf.pair_of_row, buf.x_perm, buf.ws)
+    gen = torch.Generator(device="cuda").manual_seed(99 + w.seed)
+    dyp = torch.randn((w.R, w.d), device="cuda", generator=gen).to(tdtype(w))
+    B.moe_grouped_ffn_fwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.y_perm, buf.a_save, buf.b_save,
+                          buf.ws)
+    B.moe_grouped_ffn_bwd(s, buf.x_perm, buf.offsets, g["w1"], g["w3"], g["w2"], buf.a_save, buf.b_save, dyp,
+                          buf.dx_perm, buf.dw1, buf.dw3, buf.dw2, buf.ws)
+    off = case.offsets.astype(np.int64)
+    G = 2 * w.E
+    go = np.empty(G + 1, np.int32)
+    go[0::2] = off                                                  # group 2e starts where expert e starts
+    go[1::2] = off[:-1] + (np.diff(off) + 1) // 2 // 8 * 8          # group 2e+1 at a multiple of 8 rows inside it
+    go_d = torch.from_numpy(go).cuda()
+    eog = torch.arange(G, dtype=torch.int32, device="cuda") // 2
+    el = dict(dtype=tdtype(w), device="cuda")
+    y2 = torch.full_like(buf.y_perm, float("nan"))
+    a2, b2 = torch.empty_like(buf.a_save), torch.empty_like(buf.b_save)
+    B.moe_grouped_ffn_fwd_groups(s, G, eog, buf.x_perm, go_d, g["w1"], g["w3"], g["w2"], y2, a2, b2, buf.ws)
+    dxp2 = torch.full_like(buf.dx_perm, float("nan"))
+    gw1 = torch.full((G, w.d, w.f), float("nan"), **el)
+    gw3 = torch.full((G, w.d, w.f), float("nan"), **el)
+    gw2 = torch.full((G, w.f, w.d), float("nan"), **el)
+    B.moe_grouped_ffn_bwd_groups(s, G, eog, buf.x_perm, go_d, g["w1"], g["w3"], g["w2"], a2, b2, dyp, dxp2, gw1, gw3,
+                                 gw2, buf.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, buf.y_perm) and torch.equal(a2, buf.a_save) and torch.equal(b2, buf.b_save)
+    assert torch.equal(dxp2, buf.dx_perm)
+    tol = TOL[tdtype(w)]
+    for name, grp, plain in (("dW1", gw1, buf.dw1), ("dW3", gw3, buf.dw3), ("dW2", gw2, buf.dw2)):
+        assert bool(torch.isfinite(grp).all()), name
+        summed = grp[0::2].float() + grp[1::2].float()
+        diff = (summed - plain.float()).abs().flatten(1).max(dim=1).values
+        scale = plain.float().abs().flatten(1).max(dim=1).values
+        for e in range(w.E):
+            if case.counts[e] == 0:
+                assert float(diff[e]) == 0.0 and float(scale[e]) == 0.0
+            else:
+                assert float(diff[e]) <= tol * float(scale[e]), (name, "expert", e, float(diff[e]), float(scale[e]))
+        # an empty group is written as zeros
+        for gi in np.nonzero(np.diff(go) == 0)[0]:
+            assert float(grp[gi].abs().max()) == 0.0
 
 
 @pytest.mark.parametrize("T,k,E", [(280_000, 8, 200), (150_001, 3, 7)])
