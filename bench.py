@@ -15,7 +15,9 @@ with HIP events recorded around them inside the timed steps; `roofline_hbm`
 prices the row-copy stages against the HBM peak; `other_workloads` holds the
 same figures for the other configurations (fewer steps); `ceilings` are what a
 plain device copy and a dense one-expert problem through the same GEMM kernel
-reach on this machine in this run; `cpu_baseline` is the CPU oracle timed on a
+reach on this machine in this run (with the vendor library's plain GEMM beside
+them); `saved_as` is a short run of the same workload with the other form of
+saved activations (--saved); `cpu_baseline` is the CPU oracle timed on a
 bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -443,6 +445,19 @@ def main():
     cpu = None
     if not args.no_cpu_baseline and not args.hot_path_only:
         cpu = cpu_baseline(w, inp)
+    if not args.hot_path_only and w.backward:
+        # the same workload with the other form of saved activations, as a short leg beside the headline
+        del buf
+        torch.cuda.empty_cache()
+        headline_form = SAVED_AS
+        SAVED_AS = "products" if headline_form == "ab" else "ab"
+        o = run_workload(w, steps=20, warmup=5, inp=inp)
+        out["saved_as"] = {"headline": headline_form,
+                           SAVED_AS: {"ms_per_step": round(o["ms_per_step"], 4), "ffn_tflops": round(o["achieved"], 1),
+                                      "frac": round(o["achieved"] / PEAK_BF16_TFLOPS, 4), "steps": 20, "warmup": 5,
+                                      "ffn_fwd_ms": o["stages"]["ffn_fwd"]["ms"], "ffn_bwd_ms": o["stages"]["ffn_bwd"]["ms"]}}
+        SAVED_AS = headline_form
+        buf = None
     del s, g, buf, inp
     torch.cuda.empty_cache()
     if not args.hot_path_only:
