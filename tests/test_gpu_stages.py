@@ -289,7 +289,10 @@ def test_run_to_run_determinism(case):
 EDGE_COUNTS = [1, 7, 31, 33, 255, 257, 0, 128, 129, 64, 2, 513]
 
 
-@pytest.mark.parametrize("d,f", [(256, 384), (192, 136)])   # the MFMA-tile kernel / the plain tiled kernel
+# (256, 384): the MFMA-tile kernel; (192, 136): f is no multiple of 64, so the GEMMs with K = f take the plain tiled
+# kernel; (64, 64): one k-stage per tile; (128, 192): two and three k-stages (the pipelined loop runs once at most);
+# (320, 264): five k-stages and a last column tile 8 wide
+@pytest.mark.parametrize("d,f", [(256, 384), (192, 136), (64, 64), (128, 192), (320, 264)])
 def test_grouped_ffn_at_tile_edges(d, f):
     """moe_grouped_ffn_fwd / _bwd driven with a chosen count vector: every expert's rows and every expert's
     weight gradients are compared with the oracle on that expert's own scale."""
@@ -331,3 +334,21 @@ def test_grouped_ffn_at_tile_edges(d, f):
         e0 = EDGE_COUNTS.index(0)
         assert float(buf.dw1[e0].abs().max()) == 0 and float(buf.dw3[e0].abs().max()) == 0 \
             and float(buf.dw2[e0].abs().max()) == 0
+    # the pair that saves products, on the same edges
+    y_plain = buf.y_perm.clone()
+    h = torch.full_like(buf.a_save, float("nan"))
+    for t in (buf.y_perm, buf.a_save, buf.b_save, buf.dx_perm, buf.dw1, buf.dw3, buf.dw2):
+        t.fill_(float("nan"))
+    B.moe_grouped_ffn_fwd_products(s, xp, off, w1, w3, w2, buf.y_perm, h, buf.a_save, buf.b_save)
+    B.moe_grouped_ffn_bwd_products(s, xp, off, w1, w3, w2, h, buf.a_save, buf.b_save, dyp, buf.dx_perm, buf.dw1,
+                                   buf.dw3, buf.dw2, buf.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.y_perm, y_plain)
+    for name, got, want, blocks in (("H", h, H, groups), ("dXp", buf.dx_perm, dxp, groups),
+                                    ("dW1", buf.dw1, dw1, range(E)), ("dW3", buf.dw3, dw3, range(E)),
+                                    ("dW2", buf.dw2, dw2, range(E))):
+        got = host(got)
+        assert np.isfinite(got).all(), name
+        assert rel_max(got, want) <= 2e-2, name
+        err, e = rel_max_blocks(got, want, blocks)
+        assert err <= 2e-2, (name, "products", "expert", e, "rows", int(counts[e]), err)
