@@ -258,6 +258,28 @@ def run_workload(w, steps, warmup, inp=None, keep=False):
     wall = time.perf_counter() - t0
 
     ms_per_step = wall * 1e3 / steps
+    # the same steps replayed from a HIP graph (the calls only enqueue kernels, so a step captures as it is):
+    # what the launch path costs, which matters for the short layers
+    graph_ms = None
+    if GRAPH_LEG:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
+        del graph
     stage_ms = {n: float(np.mean([marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(steps)]))
                 for j, n in enumerate(stage_names)}
     counts = buf.counts.cpu().numpy()
@@ -288,7 +310,7 @@ def run_workload(w, steps, warmup, inp=None, keep=False):
         hbm_stage("combine_bwd", cbwd_bytes)
     res = {"ms_per_step": ms_per_step, "tokens_per_s": w.T / (ms_per_step * 1e-3), "stages": stages, "hbm": hbm,
            "achieved": achieved, "flops": flops, "ffn_ms": ffn_ms, "counts": counts,
-           "perm_bytes": perm_bytes, "comb_bytes": comb_bytes,
+           "perm_bytes": perm_bytes, "comb_bytes": comb_bytes, "graph_ms": graph_ms,
            "config": {"workload": w.name, "T": w.T, "d": w.d, "f": w.f, "E": w.E, "k": w.k,
                       "pass": "fwd+bwd" if w.backward else "fwd", "seed": w.seed,
                       "max_over_mean_load": float(counts.max() / counts.mean()),
@@ -363,12 +385,14 @@ def ceilings_leg():
 # What the forward pass keeps for the backward pass: "ab" = A and B (moe_grouped_ffn_fwd/_bwd), "products" = H,
 # B*silu'(A) and silu(A) (moe_grouped_ffn_fwd_products/_bwd_products: one more saved tensor, a cheaper backward)
 SAVED_AS = "ab"
+# also time the steps replayed from a captured HIP graph (off for the runs the profiles are taken on)
+GRAPH_LEG = True
 
 OTHER_WORKLOADS = ["cfg2_e64k4", "cfg4_finegrained", "cfg5_skewed", "cfg5_balanced"]
 
 
 def main():
-    global SAVED_AS
+    global SAVED_AS, GRAPH_LEG
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
@@ -386,6 +410,7 @@ def main():
                     help="run only a plain 1 GiB device copy a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
     SAVED_AS = args.saved
+    GRAPH_LEG = not args.hot_path_only
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the hot path of one device's token share); "
               "--gpus must be 1", file=sys.stderr)
@@ -436,6 +461,9 @@ def main():
         "roofline_hbm": {"bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s", "stages": r["hbm"]},
         "stages": r["stages"],
     }
+    if r["graph_ms"] is not None:
+        out["hip_graph_replay"] = {"ms_per_step": round(r["graph_ms"], 4), "steps": args.steps,
+                                   "note": "the same step captured once and replayed; the headline is the eager loop"}
     if not args.hot_path_only:
         out["cold_cache"] = cold_leg(w, s, g, buf, r["perm_bytes"], r["comb_bytes"])
         for n in ("permute", "combine"):
@@ -483,6 +511,7 @@ def main():
                             "pass": o["config"]["pass"], "max_over_mean_load": o["config"]["max_over_mean_load"],
                             "empty_experts": o["config"]["empty_experts"], "steps": o_steps, "warmup": 10,
                             "ffn_tflops": round(o["achieved"], 1), "frac": round(o["achieved"] / PEAK_BF16_TFLOPS, 4),
+                            "hip_graph_replay_ms_per_step": None if o["graph_ms"] is None else round(o["graph_ms"], 4),
                             "hbm": {n: {"gbs": v["achieved"], "frac": v["frac"]} for n, v in o["hbm"].items()}}
             torch.cuda.empty_cache()
         if "cfg5_skewed" in others and "cfg5_balanced" in others:
