@@ -270,14 +270,14 @@ def test_grouped_ffn_backward_sampled(case):
     check("products saved")
 
 
+@pytest.mark.parametrize("case", ["cfg3_mixtral", "cfg4_finegrained", "mixtral8x7b_e16k4"], indirect=True)
 def test_backward_over_two_groups_per_expert(case):
     """A property that holds at any size: cut every expert's rows into two replica groups (G = 2E, the second
     group may be empty).  The layer output and dXp are per-row results and must keep their bits; the two groups'
     weight gradients add up to the expert's (each is rounded to the storage type once, so the sum sits within
     the bar of the plain gradient, expert by expert)."""
     w, s, g = case.w, case.s, case.g
-    if not w.backward or 2 * w.E > 256 or w.name not in ("cfg3_mixtral", "cfg4_finegrained", "mixtral8x7b_e16k4"):
-        pytest.skip("run on three backward workloads with 2E <= 256")
+    assert w.backward and 2 * w.E <= 256
     buf = MoeLayerBuffers(s, backward=True)
     ids = torch.from_numpy(case.ids).cuda()
     B.moe_permute(s, g["x"], ids, buf.counts, buf.offsets, buf.row_of_pair, buf.pair_of_row, buf.x_perm, buf.ws)
